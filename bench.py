@@ -1,0 +1,329 @@
+#!/usr/bin/env python3
+"""Benchmark of the cached-prefill hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic conversations, for every
+layer of the stack:  rebase (once)  ->  per layer: load kept history into the paged pool,
+append the new turn's K/V, fused rotary + causal attention of the new tokens, save the new
+turn's K/V (pre-rotary) back to the tier.
+
+Headline (`value`): new-turn tokens per second of the whole stack with the KV tier RESIDENT IN
+HBM when the timed region starts (the tier buffers are device memory; the same entry points
+run, the load kernel reads the tier in place).  The PCIe-inclusive pipeline (tier in pinned host
+memory, hipMemcpyAsync on the library's copy stream overlapped with attention) is measured in a
+second, shorter leg and reported under "pipeline"; it is never `value`.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+P = 16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload index 1..5 (default 2: LLaMA-7B shapes, batch 16)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-pipeline", action="store_true", help="skip the pinned-host (PCIe-inclusive) leg")
+    ap.add_argument("--pipeline-steps", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging only; marks the result invalid)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2403_19708_amd as ca
+    from synth import CONFIGS, bf16_bits_to_f64, draw_block_table, draw_values_bf16, make_workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = make_workload(args.config, seed=args.seed)
+    cfg = wl.cfg
+    L = args.layers or cfg["n_layers"]
+    Hq, Hkv, D, B, W = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["batch"], cfg["window"]
+    hist, new = wl.hist_len, wl.new_len
+    if cfg["truncate"]:
+        keep_start = ca.truncate_plan(hist, new, W, cfg["ratio"], policy=0)
+    else:
+        keep_start = np.zeros(B, np.int32)
+    n_keep = hist - keep_start
+    ctx_len = n_keep + new
+    pages = (ctx_len + P - 1) // P
+    num_pages = int(pages.sum()) + 8
+    block_table = draw_block_table(pages, num_pages, args.seed + 17)
+    tot_q, tot_n, tot_k = int(new.sum()), int(n_keep.sum()), int(ctx_len.sum())
+    cu_q = np.concatenate([[0], np.cumsum(new)]).astype(np.int64)
+    row = Hkv * D            # elements per token on the KV side
+    scale = 1.0 / np.sqrt(D)
+    log(f"[bench] {cfg['name']}: L={L} B={B} Hq={Hq} Hkv={Hkv} D={D} kept-history={tot_n} new={tot_q} tokens")
+
+    # ---- algorithmic work per layer (one launch of each kernel) ---------------------------------
+    flops_layer = 4.0 * D * Hq * float(np.sum(new.astype(np.float64) * n_keep + new.astype(np.float64) * (new + 1) / 2))
+    attn_bytes = 2.0 * tot_k * row * 2 + 2.0 * tot_q * Hq * D * 2        # K,V once + Q in + O out
+    unpack_bytes = 2.0 * (2.0 * tot_n * row * 2)                         # read + write, K and V
+    append_bytes = 2.0 * (2.0 * tot_q * row * 2)
+    pack_bytes = 2.0 * (2.0 * tot_q * row * 2)
+    link_in_bytes = 2.0 * tot_n * row * 2
+    link_out_bytes = 2.0 * tot_q * row * 2
+
+    # ---- device tensors ----------------------------------------------------------------------------
+    def bits_to_dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234 + args.seed)
+
+    def randn(shape):
+        return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    # tier: per layer one K and one V buffer holding every conversation's [hist + new] tokens
+    tier_off = np.concatenate([[0], np.cumsum(hist.astype(np.int64) + new)])
+    t0 = time.time()
+    layer0 = {}
+    for name, toks in (("k_hist", hist), ("v_hist", hist), ("q", new), ("k_new", new), ("v_new", new)):
+        heads = Hq if name == "q" else Hkv
+        layer0[name] = [draw_values_bf16((int(toks[c]), heads, D), args.seed, wl.stream(0, name, c)) for c in range(B)]
+    tier_k, tier_v, k_pool, v_pool, q, k_new, v_new, out = [], [], [], [], [], [], [], []
+    for l in range(L):
+        tk = torch.empty((int(tier_off[-1]), Hkv, D), dtype=torch.bfloat16, device=dev)
+        tv = torch.empty_like(tk)
+        if l == 0:
+            for c in range(B):
+                a = int(tier_off[c])
+                tk[a:a + int(hist[c])] = bits_to_dev(layer0["k_hist"][c])
+                tv[a:a + int(hist[c])] = bits_to_dev(layer0["v_hist"][c])
+            q.append(bits_to_dev(np.concatenate(layer0["q"])))
+            k_new.append(bits_to_dev(np.concatenate(layer0["k_new"])))
+            v_new.append(bits_to_dev(np.concatenate(layer0["v_new"])))
+        else:
+            tk.copy_(randn(tk.shape))
+            tv.copy_(randn(tv.shape))
+            q.append(randn((tot_q, Hq, D)))
+            k_new.append(randn((tot_q, Hkv, D)))
+            v_new.append(randn((tot_q, Hkv, D)))
+        tier_k.append(tk)
+        tier_v.append(tv)
+        k_pool.append(torch.zeros((num_pages, Hkv, P, D), dtype=torch.bfloat16, device=dev))
+        v_pool.append(torch.zeros((num_pages, Hkv, P, D), dtype=torch.bfloat16, device=dev))
+        out.append(torch.zeros((tot_q, Hq, D), dtype=torch.bfloat16, device=dev))
+    torch.cuda.synchronize()
+    log(f"[bench] inputs ready in {time.time() - t0:.1f}s, {torch.cuda.memory_allocated() / 2**30:.1f} GiB on device")
+
+    def tier_ptrs(bufs, layer):
+        base, esz = bufs[layer].data_ptr(), row * 2
+        return [base + int(tier_off[c]) * esz for c in range(B)]
+
+    conf = ca.Config(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=W,
+                     pipeline_depth=2, max_seqs=B, max_batch_kv_tokens=tot_k + 64, max_batch_q_tokens=tot_q + 16)
+    ctx = ca.Context(conf)
+    stream = torch.cuda.current_stream()
+
+    def step(src_k, src_v):
+        ctx.rope_rebase(hist, keep_start, new, block_table, num_pages, stream)
+        for l in range(L):
+            ctx.kv_load_layer(l, src_k[l], src_v[l], k_pool[l], v_pool[l])
+        for l in range(L):
+            ctx.kv_append_layer(l, k_new[l], v_new[l], k_pool[l], v_pool[l], stream)
+            ctx.cached_prefill_attn(l, q[l], k_pool[l], v_pool[l], out[l], scale, stream)
+            ctx.kv_save_layer(l, k_pool[l], v_pool[l], src_k[l], src_v[l], after_stream=stream)
+        ctx.join(stream)
+
+    def timed(src_k, src_v, warmup, steps, tag):
+        for i in range(warmup):
+            step(src_k, src_v)
+        ctx.sync(); torch.cuda.synchronize()
+        for k in ca.Context.PROFILE_KINDS:
+            ctx.profile_read(k)              # drop what the warmup recorded
+        ctx.profile_enable(True)
+        t = time.perf_counter()
+        for i in range(steps):
+            step(src_k, src_v)
+        ctx.sync(); torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        ctx.profile_enable(False)
+        prof = {k: ctx.profile_read(k) for k in ca.Context.PROFILE_KINDS}
+        log(f"[bench] {tag}: {steps} steps in {dt * 1e3:.1f} ms")
+        return dt, prof
+
+    # ---- leg 1: tier resident in HBM (the headline) ---------------------------------------------------
+    dev_k = [tier_ptrs(tier_k, l) for l in range(L)]
+    dev_v = [tier_ptrs(tier_v, l) for l in range(L)]
+    dt, prof = timed(dev_k, dev_v, args.warmup, args.steps, "HBM-resident tier")
+    ms_step = dt / args.steps * 1e3
+    value = tot_q / (dt / args.steps)
+
+    def avg_us(kind):
+        ms, n = prof[kind]
+        return (ms / n * 1e3) if n else None
+
+    kern = {
+        "attn": dict(us=avg_us("attn"), bytes=attn_bytes, flops=flops_layer),
+        "unpack": dict(us=avg_us("unpack"), bytes=unpack_bytes),
+        "append": dict(us=avg_us("append"), bytes=append_bytes),
+        "pack": dict(us=avg_us("pack"), bytes=pack_bytes),
+    }
+    for k, v in kern.items():
+        v["gbs"] = v["bytes"] / (v["us"] * 1e-6) / 1e9 if v["us"] else None
+    attn_tflops = flops_layer / (kern["attn"]["us"] * 1e-6) / 1e12
+    t_mfma_us = flops_layer / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6
+    t_hbm_us = attn_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
+    attn_bound = "mfma" if t_mfma_us > t_hbm_us else "hbm"
+    # the dominant kernel is the one with the largest share of a step's GPU time
+    dominant = max(kern, key=lambda k: kern[k]["us"] or 0.0)
+    if dominant == "attn" and attn_bound == "mfma":
+        roof = dict(kernel="attn_mfma_kernel", bound="mfma", achieved=attn_tflops, peak=MFMA_BF16_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=attn_tflops / MFMA_BF16_PEAK_TFLOPS, traffic=None)
+    else:
+        name = {"attn": "attn_mfma_kernel", "unpack": "move_kernel<to_pool> (load)", "append": "move_kernel<to_pool> (append)",
+                "pack": "move_kernel<from_pool> (save)"}[dominant]
+        roof = dict(kernel=name, bound="hbm", achieved=kern[dominant]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=kern[dominant]["gbs"] / HBM_PEAK_GBS, traffic=None)
+    roof["avg_launch_us"] = kern[dominant]["us"]
+    roof["algorithmic_bytes_per_launch"] = kern[dominant]["bytes"]
+
+    # ---- sampled parity check of layer 0 against the oracle ---------------------------------------------
+    parity = None
+    if not args.no_check:
+        import oracle
+        got_all = out[0].detach().cpu().view(torch.int16).numpy().view(np.uint16)
+        rng = np.random.default_rng(5)
+        samples = [(int(rng.integers(B)), int(rng.integers(Hq))) for _ in range(6)]
+        G = Hq // Hkv
+        worst_max, worst_mean = 0.0, 0.0
+        for c, h in samples:
+            g = h // G
+            w = bf16_bits_to_f64
+            want = oracle.cached_attention(w(layer0["k_hist"][c][:, g:g + 1]), w(layer0["v_hist"][c][:, g:g + 1]),
+                                           w(layer0["q"][c][:, h:h + 1]), w(layer0["k_new"][c][:, g:g + 1]),
+                                           w(layer0["v_new"][c][:, g:g + 1]), keep_start=int(keep_start[c]))
+            got = w(got_all[int(cu_q[c]):int(cu_q[c + 1]), h:h + 1])
+            err = np.abs(got - want)
+            worst_max, worst_mean = max(worst_max, float(err.max())), max(worst_mean, float(err.mean()))
+        parity = dict(samples=len(samples), max_abs=worst_max, mean_abs=worst_mean, ok=bool(worst_max <= 2e-2 and worst_mean <= 2e-3))
+        log(f"[bench] sampled parity vs oracle (layer 0): max-abs {worst_max:.2e} mean-abs {worst_mean:.2e}")
+        if not parity["ok"]:
+            log("[bench] PARITY FAILED: the numbers below are not valid")
+
+    # ---- leg 2: tier in pinned host memory, copies overlapped with attention ---------------------------------
+    pipeline = None
+    if not args.no_pipeline:
+        try:
+            t0 = time.time()
+            pin_k = [torch.empty(tier_k[l].shape, dtype=torch.bfloat16, pin_memory=True) for l in range(L)]
+            pin_v = [torch.empty(tier_v[l].shape, dtype=torch.bfloat16, pin_memory=True) for l in range(L)]
+            for l in range(L):
+                pin_k[l].copy_(tier_k[l]); pin_v[l].copy_(tier_v[l])
+            torch.cuda.synchronize()
+            log(f"[bench] pinned tier of {2 * L * tier_k[0].numel() * 2 / 2**30:.1f} GiB ready in {time.time() - t0:.1f}s")
+            host_k = [tier_ptrs(pin_k, l) for l in range(L)]
+            host_v = [tier_ptrs(pin_v, l) for l in range(L)]
+            pdt, pprof = timed(host_k, host_v, 1, args.pipeline_steps, "pinned-host tier")
+            t_pipe = pdt / args.pipeline_steps
+            cin_ms, cin_n = pprof["copy_in"]; cout_ms, cout_n = pprof["copy_out"]
+            att_ms, att_n = pprof["attn"]
+            sum_copy = (cin_ms + cout_ms) / args.pipeline_steps / 1e3
+            sum_attn = att_ms / args.pipeline_steps / 1e3
+            pipeline = dict(
+                tokens_per_s=tot_q / t_pipe, context_tokens_per_s=tot_k / t_pipe, ms_per_step=t_pipe * 1e3,
+                h2d_gbs=link_in_bytes * cin_n / (cin_ms * 1e-3) / 1e9 if cin_ms else None,
+                d2h_gbs=link_out_bytes * cout_n / (cout_ms * 1e-3) / 1e9 if cout_ms else None,
+                sum_copy_ms=sum_copy * 1e3, sum_attn_ms=sum_attn * 1e3,
+                overlap_efficiency=(sum_copy + sum_attn - t_pipe) / min(sum_copy, sum_attn) if min(sum_copy, sum_attn) > 0 else None,
+                link_bound_floor_ms=sum_copy * 1e3,
+            )
+            del pin_k, pin_v
+        except Exception as e:  # the pinned leg is secondary; report why it is missing
+            log(f"[bench] pinned-host leg failed: {e!r}")
+            pipeline = dict(error=repr(e))
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample --------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        w = bf16_bits_to_f64
+        budget_s, used, convs, fl = 20.0, 0.0, 0, 0.0
+        t_start = time.perf_counter()
+        for c in range(B):
+            tk = time.perf_counter()
+            oracle.cached_attention(w(layer0["k_hist"][c]), w(layer0["v_hist"][c]), w(layer0["q"][c]),
+                                    w(layer0["k_new"][c]), w(layer0["v_new"][c]), keep_start=int(keep_start[c]))
+            used += time.perf_counter() - tk
+            convs += 1
+            fl += 4.0 * D * Hq * (float(new[c]) * float(n_keep[c]) + float(new[c]) * (float(new[c]) + 1) / 2)
+            if time.perf_counter() - t_start > budget_s:
+                break
+        # scale the sample to one whole step by its share of the step's attention flops
+        step_s = used * (flops_layer * L) / fl
+        cpu = dict(value=tot_q / step_s, unit="tokens/s", cores=oracle.n_threads(), kind="oracle",
+                   sample=f"attention of layer 0, conversations 0..{convs - 1} of {B} (all heads), {used:.1f} s of oracle time, "
+                          f"scaled to {L} layers x {B} conversations by attention flops; data movement not included",
+                   gflops=fl / used / 1e9)
+        log(f"[bench] oracle: {convs} conversations of one layer in {used:.1f}s on {cpu['cores']} threads")
+
+    result = {
+        "metric": "cached-prefill tokens/s + attn TFLOP/s (% bf16 MFMA peak); KV load/pack GB/s",
+        "value": value,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg["name"], "index": args.config, "n_layers": L, "batch": B, "n_q_heads": Hq,
+                   "n_kv_heads": Hkv, "head_dim": D, "new_tokens": tot_q, "kept_history_tokens": tot_n,
+                   "tier": "HBM-resident", "valid": not bool(args.layers)},
+        "context_tokens_per_s": tot_k / (dt / args.steps),
+        "attn": {"tflops": attn_tflops, "frac_mfma_peak": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                 "avg_launch_us": kern["attn"]["us"], "gbs": kern["attn"]["gbs"], "frac_hbm_peak": kern["attn"]["gbs"] / HBM_PEAK_GBS,
+                 "binding_roofline": attn_bound, "roofline_floor_us": max(t_mfma_us, t_hbm_us),
+                 "frac_binding_roofline": max(t_mfma_us, t_hbm_us) / kern["attn"]["us"]},
+        "kv_move": {k: {"avg_launch_us": kern[k]["us"], "gbs": kern[k]["gbs"],
+                        "frac_hbm_peak": (kern[k]["gbs"] / HBM_PEAK_GBS) if kern[k]["gbs"] else None}
+                    for k in ("unpack", "append", "pack")},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "pipeline": pipeline,
+        "parity": parity,
+    }
+    print(json.dumps(result), flush=True)
+    ctx.close()
+    return 0 if (parity is None or parity["ok"]) else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())

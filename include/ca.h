@@ -1,0 +1,203 @@
+/*
+ * ca.h - C ABI of the CachedAttention new-turn prefill path for AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels on ONE GPU, the part of
+ * CachedAttention (arXiv 2403.19708) that runs for every new conversation turn:
+ *
+ *   save   (Section 3.2.2) keys/values leave HBM layer by layer on a write stream; keys
+ *                          are stored WITHOUT positional encoding (Section 3.4).
+ *   load   (Section 3.2.1) the saved history of layer l is brought back into the paged
+ *                          HBM pool on a read stream while earlier layers compute.
+ *   rebase (Section 3.4)   after context-window truncation the kept tokens are numbered
+ *                          again from 0; the rotary encoding is embedded at these new
+ *                          positions when the cache is used.
+ *   attend (Sections 2.1, 3.1) only the new tokens are prefilled: their queries attend
+ *                          to [kept history | new tokens] with a causal mask.
+ *
+ * Conventions
+ *   - Plain C types only.  "device" pointers are HIP device memory, "host" pointers are
+ *     ordinary host memory unless "pinned" is stated (then hipHostMalloc'd / torch
+ *     pin_memory).  Streams are hipStream_t passed as void*; NULL is the default stream.
+ *   - The caller owns every tensor (pools, Q, output, host tier).  The library owns its
+ *     context: three internal streams (copy-in, unpack, save), events, a ring of staging
+ *     slots in HBM, a rotary table and small per-batch metadata.  It never frees or
+ *     reallocates caller memory.
+ *   - Every call validates its arguments on the host BEFORE anything is launched and
+ *     returns a ca_status; nothing throws or aborts.  ca_last_error() gives the text of
+ *     the last failure on that context.  A context is not thread-safe.
+ *   - All entry points except ca_create / ca_destroy / ca_sync / ca_rebase_read are
+ *     asynchronous with respect to the host.
+ *
+ * Layouts (element type bf16 = 2 bytes unless stated)
+ *   paged pool   k_pool, v_pool : [num_pages][n_kv_heads][page_size][head_dim], one pair
+ *                per layer; keys in the pool carry NO positional encoding.
+ *   contiguous   per conversation and layer: [tokens][n_kv_heads][head_dim] (what the
+ *                host tier stores; token 0 is the oldest saved token).
+ *   q, out       [sum new_len][n_q_heads][head_dim], conversations concatenated in batch
+ *                order; q carries NO positional encoding.
+ *   block_table  [n_seqs][max_pages] int32 physical page ids; context token t of
+ *                conversation c lives in page block_table[c][t / page_size], slot
+ *                t % page_size.  The context of c is [kept history | new tokens].
+ *   Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ */
+#ifndef CA_H_
+#define CA_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ca_ctx ca_ctx;
+
+typedef enum {
+    CA_OK = 0,
+    CA_ERR_INVALID_ARG = 1,  /* null pointer, negative size, inconsistent lengths            */
+    CA_ERR_OUT_OF_RANGE = 2, /* layer, page id, token range or batch size beyond a limit      */
+    CA_ERR_UNSUPPORTED = 3,  /* head_dim / page_size / style the kernels are not built for    */
+    CA_ERR_NOMEM = 4,        /* context allocation failed                                     */
+    CA_ERR_NOT_READY = 5,    /* call order: no rebase yet, layer not loaded, loaded twice     */
+    CA_ERR_HIP = 6           /* a HIP runtime call failed; text in ca_last_error()            */
+} ca_status;
+
+typedef struct {
+    int32_t n_layers;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;      /* divides n_q_heads                                             */
+    int32_t head_dim;        /* 64 or 128                                                     */
+    int32_t page_size;       /* tokens per page; 16                                           */
+    int32_t max_positions;   /* context window W: largest context (kept history + new) + 0    */
+    float   rope_base;       /* 10000                                                         */
+    int32_t rope_style;      /* 0: pairs (i, i + head_dim/2); 1: pairs (2i, 2i+1)             */
+    int32_t pipeline_depth;  /* staging slots for loads (read buffer) and for saves, >= 1     */
+    int32_t max_seqs;        /* largest batch                                                 */
+    int64_t max_batch_kv_tokens; /* largest sum over the batch of context tokens; sizes one   */
+                                 /* staging slot and the metadata                             */
+    int64_t max_batch_q_tokens;  /* largest sum over the batch of new tokens                  */
+    int32_t load_mode;       /* 0: choose per source pointer; 1: copy into a staging slot,    */
+                             /* then unpack; 2: the unpack kernel reads the source in place   */
+                             /* (source must be device-accessible)                            */
+    int32_t attn_variant;    /* 0: MFMA kernel; 1: scalar fp32 kernel (slow, for checking)    */
+    int32_t require_load;    /* 1: attention on a layer with kept history that was not loaded */
+                             /* under the current plan fails with CA_ERR_NOT_READY            */
+    int32_t device;          /* HIP device ordinal                                            */
+} ca_config;
+
+/* One batch of conversations about to run a new turn.  All pointers are HOST memory and are
+ * read during ca_rope_rebase only.  keep_start[c] in [0, hist_len[c]] is the first saved token
+ * that survives truncation; n_keep = hist_len - keep_start; context = n_keep + new_len.       */
+typedef struct {
+    int32_t n_seqs;
+    const int32_t *hist_len;    /* [n_seqs] tokens saved in the host tier                     */
+    const int32_t *keep_start;  /* [n_seqs]                                                   */
+    const int32_t *new_len;     /* [n_seqs] >= 1                                              */
+    const int32_t *block_table; /* [n_seqs][max_pages]; the first ceil(context/page_size)     */
+                                /* entries of a row must be distinct valid pages              */
+    int32_t max_pages;
+    int32_t num_pages;          /* pages in every pool later passed with this batch           */
+} ca_batch;
+
+/* ---- context ------------------------------------------------------------------------ */
+
+/* Fills *cfg with defaults (page 16, base 10000, half-split pairs, depth 2, MFMA kernel). */
+void ca_config_default(ca_config *cfg);
+
+/* Host-only checks of a configuration / a batch against a configuration.  Used by every
+ * entry point; exported so that callers (and CPU-only tests) can check without a GPU.
+ * err, if not NULL, receives a message of at most err_len bytes.                           */
+ca_status ca_config_validate(const ca_config *cfg, char *err, int32_t err_len);
+ca_status ca_batch_validate(const ca_config *cfg, const ca_batch *batch, char *err, int32_t err_len);
+
+/* Allocates the context on cfg->device: streams, events, staging ring
+ * (2 * pipeline_depth slots of 2 * max_batch_kv_tokens * n_kv_heads * head_dim * 2 bytes),
+ * rotary table (max_positions * head_dim/2 cos/sin pairs, fp32, computed in fp64), metadata. */
+ca_status ca_create(const ca_config *cfg, ca_ctx **out);
+void ca_destroy(ca_ctx *ctx);
+const char *ca_last_error(const ca_ctx *ctx);
+const char *ca_status_string(ca_status s);
+
+/* ---- Section 3.4 / 4.1: truncation planner (host only, no context needed) ----------- */
+/* keep_start_out[c] = 0 unless hist_len[c] + new_len[c] > window.  On overflow the most recent
+ * tokens survive:  policy 0 keeps floor(window*(1-ratio)) tokens of [history|new] (the new turn
+ * is never dropped); policy 1 drops floor(window*ratio) oldest tokens, repeatedly while the
+ * context still overflows; policy 2 drops floor(ratio*context) oldest tokens, repeatedly.
+ * 0 < ratio < 1.  Arrays are host memory of n entries.                                       */
+ca_status ca_truncate_plan(const int32_t *hist_len, const int32_t *new_len, int32_t window,
+                           double ratio, int32_t policy, int32_t n, int32_t *keep_start_out);
+
+/* ---- Section 3.4: position rebasing --------------------------------------------------- */
+/* Makes `batch` the context's current plan: numbers the kept tokens of every conversation
+ * from 0 (keys 0..context-1, new token j at n_keep + j), and builds on the device the
+ * metadata the other calls use (prefix sums, per-token positions and page slots, the
+ * attention work list).  Host arrays of `batch` may be reused when the call returns.
+ * Ordering: work queued earlier on `stream` and on the internal streams completes before
+ * the metadata changes; later calls on this context see the new plan.                       */
+ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *batch, void *stream);
+
+/* Copies a piece of the current plan's device metadata to host (synchronises; for tests and
+ * debugging).  which: 0 n_keep[n_seqs], 1 cu_q[n_seqs+1], 2 cu_k[n_seqs+1], 3 q_pos[sum new],
+ * 4 q_seq[sum new], 5 slot_map[sum context] (page*page_size + slot of every context token),
+ * 6 attention work list (4 int32 per item: seq, kv_head, first_row, n_rows; seq -1 = padding).
+ * capacity is in int32 elements; *count receives the number written.                         */
+ca_status ca_rebase_read(ca_ctx *ctx, int32_t which, int32_t *out, int64_t capacity, int64_t *count);
+
+/* ---- Section 3.2.1: layer-wise loading -------------------------------------------------- */
+/* Brings the kept history of `layer` into the pools: for every conversation c the tokens
+ * [keep_start[c], hist_len[c]) of src_k[c] / src_v[c] (contiguous layout, pointer to saved
+ * token 0 of this layer; host array of n_seqs pointers) become context tokens [0, n_keep[c]).
+ * Truncation is just the source offset.  Runs on the internal copy-in and unpack streams and
+ * marks the layer ready; ca_cached_prefill_attn(layer) waits for that mark on its own stream.
+ * Sources: pinned host memory (staged hipMemcpyAsync into a ring slot + unpack kernel, or read
+ * in place by the unpack kernel, see load_mode) or device memory (read in place).  A layer can
+ * be loaded once per plan (CA_ERR_NOT_READY otherwise).                                        */
+ca_status ca_kv_load_layer(ca_ctx *ctx, int32_t layer, const void *const *src_k,
+                           const void *const *src_v, void *k_pool, void *v_pool);
+
+/* Writes the new turn's keys/values (device, [sum new_len][n_kv_heads][head_dim], no positional
+ * encoding) behind the kept history, context tokens [n_keep[c], n_keep[c]+new_len[c]), on
+ * `stream`.  This is the hand-over point from the K/V projections of a model.                 */
+ca_status ca_kv_append_layer(ca_ctx *ctx, int32_t layer, const void *new_k, const void *new_v,
+                             void *k_pool, void *v_pool, void *stream);
+
+/* ---- Sections 2.1, 3.1, 3.4: prefill of the new tokens over the reused cache ------------ */
+/* out[j, h, :] = sum_t softmax_t( RoPE(q[j,h], n_keep+j) . RoPE(k[t, h/G], t) * softmax_scale ) v[t, h/G]
+ * over context tokens t <= n_keep + j of the same conversation.  The rotary encoding is applied
+ * to keys as they are read from the pool; the pool is not modified.  bf16 in, fp32 accumulate,
+ * bf16 out.  q, out: device.  Waits (on `stream`) for the load of `layer` if one was issued.   */
+ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, const void *k_pool,
+                                 const void *v_pool, void *out, float softmax_scale, void *stream);
+
+/* ---- Section 3.2.2: asynchronous saving --------------------------------------------------- */
+/* Copies context tokens [tok_begin[c], tok_end[c]) of every conversation (host int32 arrays;
+ * NULL means the new tokens [n_keep, n_keep+new_len)) out of the pools into dst_k[c] / dst_v[c]
+ * (contiguous layout, pointer to saved token 0) starting at token dst_tok_offset[c] (host int64
+ * array; NULL means hist_len[c], i.e. append behind the saved history).  Keys leave without
+ * positional encoding, exactly as stored.  Runs on the internal save stream after the work
+ * queued so far on `after_stream`.  Destinations: pinned host (pack kernel into a ring slot +
+ * hipMemcpyAsync) or device memory (written in place by the pack kernel).                     */
+ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
+                           const int32_t *tok_end, const void *k_pool, const void *v_pool,
+                           void *const *dst_k, void *const *dst_v, const int64_t *dst_tok_offset,
+                           void *after_stream);
+
+/* Blocks the host until the internal streams are idle. */
+ca_status ca_sync(ca_ctx *ctx);
+
+/* Makes `stream` wait (device side) for everything queued so far on the internal streams. */
+ca_status ca_join(ca_ctx *ctx, void *stream);
+
+/* ---- timing of the library's own GPU work ------------------------------------------------ */
+/* While enabled, every copy batch and kernel the library queues is bracketed by HIP events on
+ * the stream it runs on (the internal streams are not visible to the caller's own events).
+ * ca_profile_read synchronises the device, returns the summed milliseconds and the number of
+ * intervals of one kind recorded since the last read of that kind, and forgets them.
+ * kind: 0 load copy-in (one interval per layer), 1 unpack kernel(s), 2 append kernel(s),
+ *       3 attention kernel, 4 pack kernel(s), 5 save copy-out (one interval per layer).        */
+ca_status ca_profile_enable(ca_ctx *ctx, int32_t on);
+ca_status ca_profile_read(ca_ctx *ctx, int32_t kind, double *total_ms, int64_t *count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CA_H_ */

@@ -1,0 +1,339 @@
+// Fused rotary-on-load + causal varlen prefill attention on the bf16 matrix cores of gfx950
+// (Sections 2.1, 3.1, 3.4): the new tokens' queries attend to [kept history | new tokens] read
+// from the paged pool; keys are stored without positional encoding and are rotated to their
+// rebased positions on the way from HBM to LDS, so the pool is never rewritten.
+//
+// Work decomposition
+//   One workgroup (4 wavefronts) owns a tile of 128 stacked query rows of one (conversation,
+//   kv head): row r is new token r / G under query head kv_head*G + r % G, so under GQA all G
+//   heads of a group share every K/V tile that is staged.  Each wavefront owns 32 rows.
+//   Keys are walked in tiles of 64.
+//
+// Matrix-core formulation (v_mfma_f32_32x32x16_bf16, operands A: 32x16, B: 16x32, C: 32x32)
+//   S^T = K Q^T : A = K tile rows from LDS, B = rotated Q held in registers.  In the C layout a
+//   lane owns ONE query column (lane % 32) and 16 keys per 32-key block, so the softmax row
+//   reductions are in-lane plus one exchange between lane l and l^32.
+//   O^T += V^T P^T : A = V^T from LDS (V is transposed on its way into LDS), B = P^T, which is
+//   exactly the C registers of S^T converted to bf16: no shuffle between the two products, and
+//   the running rescale factor is a per-lane scalar.  The key order inside a 16-key group that
+//   the C layout imposes on P^T is applied to V^T when it is written to LDS.
+//
+// Rounding: rotation in fp32 from bf16 inputs, result rounded (RNE) to bf16; scores, softmax
+// statistics and both accumulators in fp32; probabilities rounded to bf16 for the second
+// product; output rounded to bf16.
+#include "ca_internal.h"
+
+namespace ca {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BM = kAttnTileRowsMfma;  // stacked query rows per workgroup
+constexpr int BN = 64;                 // keys per tile
+constexpr int NTHREADS = 256;
+
+__device__ inline float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ inline uint32_t pack_bf16(float a, float b) {
+    bf16x2 v = {(__bf16)a, (__bf16)b};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// Rotates the 8+8 elements of two 16-byte pieces `a` (dims d0..d0+7) and `b` in fp32 and rounds
+// to bf16.  STYLE 0: element e of `a` pairs with element e of `b` (dims i and i + D/2), cs[e] is
+// the (cos, sin) of pair d0+e.  STYLE 1: neighbours pair up inside each piece; cs[0..3] belong
+// to `a`, cs[4..7] to `b`.
+template <int STYLE>
+__device__ inline void rotate16(uint4 &a, uint4 &b, const float2 (&cs)[8]) {
+    uint32_t *pa = reinterpret_cast<uint32_t *>(&a);
+    uint32_t *pb = reinterpret_cast<uint32_t *>(&b);
+    if (STYLE == 0) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float a0 = bf_lo(pa[w]), a1 = bf_hi(pa[w]);
+            const float b0 = bf_lo(pb[w]), b1 = bf_hi(pb[w]);
+            const float2 c0 = cs[2 * w], c1 = cs[2 * w + 1];
+            pa[w] = pack_bf16(a0 * c0.x - b0 * c0.y, a1 * c1.x - b1 * c1.y);
+            pb[w] = pack_bf16(b0 * c0.x + a0 * c0.y, b1 * c1.x + a1 * c1.y);
+        }
+    } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float a0 = bf_lo(pa[w]), a1 = bf_hi(pa[w]);
+            const float b0 = bf_lo(pb[w]), b1 = bf_hi(pb[w]);
+            const float2 ca_ = cs[w], cb_ = cs[4 + w];
+            pa[w] = pack_bf16(a0 * ca_.x - a1 * ca_.y, a1 * ca_.x + a0 * ca_.y);
+            pb[w] = pack_bf16(b0 * cb_.x - b1 * cb_.y, b1 * cb_.x + b0 * cb_.y);
+        }
+    }
+}
+
+template <int D, int STYLE>
+__device__ inline void load_cs(const float2 *__restrict__ rope, int pos, int piece, float2 (&cs)[8]) {
+    constexpr int HALF = D / 2;
+    const float2 *row = rope + (int64_t)pos * HALF;
+    if (STYLE == 0) {
+        const float4 *p = reinterpret_cast<const float4 *>(row + 8 * piece);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float4 v = p[w];
+            cs[2 * w] = make_float2(v.x, v.y);
+            cs[2 * w + 1] = make_float2(v.z, v.w);
+        }
+    } else {
+        const float4 *p = reinterpret_cast<const float4 *>(row + 4 * piece);
+        const float4 *q = reinterpret_cast<const float4 *>(row + HALF / 2 + 4 * piece);
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            const float4 v = p[w], u = q[w];
+            cs[2 * w] = make_float2(v.x, v.y);
+            cs[2 * w + 1] = make_float2(v.z, v.w);
+            cs[4 + 2 * w] = make_float2(u.x, u.y);
+            cs[4 + 2 * w + 1] = make_float2(u.z, u.w);
+        }
+    }
+}
+
+template <int D, int STYLE>
+__global__ __launch_bounds__(NTHREADS) void attn_mfma_kernel(AttnArgs a) {
+    constexpr int HALF = D / 2;
+    constexpr int KSTEPS = D / 16;      // k-steps of the S^T product
+    constexpr int PIECES = D / 16;      // 16-byte pieces in half a row
+    constexpr int DBLKS = D / 32;       // 32-row blocks of O^T
+    constexpr int KS_STRIDE = D + 8;    // bf16 elements; +16 bytes keeps ds_read_b128 conflict-free
+    constexpr int VT_STRIDE = BN + 8;
+
+    __shared__ __attribute__((aligned(16))) uint16_t Ks[BN * KS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t Vt[D * VT_STRIDE];
+
+    const WorkItem item = a.items[blockIdx.x];
+    if (item.seq < 0) return;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int lq = lane & 31;
+    const int half = lane >> 5;
+
+    const int c = item.seq;
+    const int g = item.kv_head;
+    const int G = a.n_q_heads / a.n_kv_heads;
+    const int n = a.n_keep[c];
+    const int q0 = a.cu_q[c];
+    const int32_t *table = a.block_table + (int64_t)c * a.max_pages;
+    const int Hkv = a.n_kv_heads;
+
+    const int row_last = item.row0 + item.n_rows - 1;          // last valid stacked row of the tile
+    const int kmax = n + row_last / G + 1;                      // keys this tile can see
+    const int n_tiles = (kmax + BN - 1) / BN;
+
+    // ---- this lane's query row --------------------------------------------------------------
+    const int r_raw = item.row0 + wave * 32 + lq;
+    const bool row_valid = r_raw <= row_last;
+    const int r = row_valid ? r_raw : row_last;
+    const int j = r / G;
+    const int head = g * G + (r - j * G);
+    const int qpos = n + j;                                      // keys 0..qpos are visible
+    // wave-uniform bounds (rows of a wave are consecutive)
+    const int wr_first = min(item.row0 + wave * 32, row_last);
+    const int wr_last = min(item.row0 + wave * 32 + 31, row_last);
+    const bool wave_live = item.row0 + wave * 32 <= row_last;
+    const int wq_min = n + wr_first / G;
+    const int wq_max = n + wr_last / G;
+
+    bf16x8 Qf[KSTEPS];
+    {
+        const uint16_t *qrow = a.q + ((int64_t)(q0 + j) * a.n_q_heads + head) * D;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS / 2; ++ks) {
+            // pieces at dims 16ks + 8half (k-step ks) and the same + D/2 (k-step ks + KSTEPS/2)
+            const int piece = 2 * ks + half;
+            uint4 x = *reinterpret_cast<const uint4 *>(qrow + 8 * piece);
+            uint4 y = *reinterpret_cast<const uint4 *>(qrow + HALF + 8 * piece);
+            float2 cs[8];
+            load_cs<D, STYLE>(a.rope, qpos, piece, cs);
+            rotate16<STYLE>(x, y, cs);
+            Qf[ks] = __builtin_bit_cast(bf16x8, x);
+            Qf[ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, y);
+        }
+    }
+
+    f32x16 O[DBLKS];
+#pragma unroll
+    for (int db = 0; db < DBLKS; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[db][i] = 0.f;
+    float m_run = -INFINITY;   // running maximum of the raw scores of this row
+    float l_run = 0.f;         // this lane's share of the running denominator
+    const float cscale = a.softmax_scale * 1.4426950408889634f;
+
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int kt0 = tile * BN;
+        __syncthreads();  // everyone is done reading the previous tile
+
+        // ---- K tile: HBM -> registers -> rotate at the key's rebased position -> LDS ---------
+#pragma unroll
+        for (int task = tid; task < BN * PIECES; task += NTHREADS) {
+            const int kk = task / PIECES;
+            const int piece = task - kk * PIECES;
+            const int t = kt0 + kk;
+            uint4 x = make_uint4(0, 0, 0, 0), y = make_uint4(0, 0, 0, 0);
+            if (t < kmax) {
+                const int page = table[t >> 4];
+                const uint16_t *krow = a.k_pool + (((int64_t)page * Hkv + g) * kPageSize + (t & 15)) * D;
+                x = *reinterpret_cast<const uint4 *>(krow + 8 * piece);
+                y = *reinterpret_cast<const uint4 *>(krow + HALF + 8 * piece);
+                float2 cs[8];
+                load_cs<D, STYLE>(a.rope, t, piece, cs);
+                rotate16<STYLE>(x, y, cs);
+            }
+            *reinterpret_cast<uint4 *>(&Ks[kk * KS_STRIDE + 8 * piece]) = x;
+            *reinterpret_cast<uint4 *>(&Ks[kk * KS_STRIDE + HALF + 8 * piece]) = y;
+        }
+
+        // ---- V tile: HBM -> registers -> 4x8 transpose -> LDS as V^T --------------------------
+        // Inside a 16-key group the C layout of S^T hands P^T to the second product in the order
+        // (half, e) <-> key (e/4)*8 + half*4 + e%4; V^T is stored in that order.
+#pragma unroll
+        for (int task = tid; task < 16 * (D / 8); task += NTHREADS) {
+            const int kq = task / (D / 8);       // quad of keys 4kq .. 4kq+3
+            const int dc = task - kq * (D / 8);  // dims 8dc .. 8dc+7
+            uint4 v[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int t = kt0 + 4 * kq + rr;
+                v[rr] = make_uint4(0, 0, 0, 0);
+                if (t < kmax) {
+                    const int page = table[t >> 4];
+                    const uint16_t *vrow = a.v_pool + (((int64_t)page * Hkv + g) * kPageSize + (t & 15)) * D;
+                    v[rr] = *reinterpret_cast<const uint4 *>(vrow + 8 * dc);
+                }
+            }
+            const int pos = (kq >> 2) * 16 + (kq & 1) * 8 + ((kq >> 1) & 1) * 4;
+            const uint32_t *w0 = reinterpret_cast<const uint32_t *>(&v[0]);
+            const uint32_t *w1 = reinterpret_cast<const uint32_t *>(&v[1]);
+            const uint32_t *w2 = reinterpret_cast<const uint32_t *>(&v[2]);
+            const uint32_t *w3 = reinterpret_cast<const uint32_t *>(&v[3]);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                // dims 8dc + 2w (low halves) and 8dc + 2w + 1 (high halves)
+                uint2 lo, hi;
+                lo.x = __builtin_amdgcn_perm(w1[w], w0[w], 0x05040100u);
+                lo.y = __builtin_amdgcn_perm(w3[w], w2[w], 0x05040100u);
+                hi.x = __builtin_amdgcn_perm(w1[w], w0[w], 0x07060302u);
+                hi.y = __builtin_amdgcn_perm(w3[w], w2[w], 0x07060302u);
+                *reinterpret_cast<uint2 *>(&Vt[(8 * dc + 2 * w) * VT_STRIDE + pos]) = lo;
+                *reinterpret_cast<uint2 *>(&Vt[(8 * dc + 2 * w + 1) * VT_STRIDE + pos]) = hi;
+            }
+        }
+        __syncthreads();
+
+        if (!wave_live || kt0 > wq_max) continue;  // nothing visible to this wavefront in the tile
+
+        // ---- S^T = K Q^T ------------------------------------------------------------------------
+        f32x16 S[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[mb][i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&Ks[(32 * mb + lq) * KS_STRIDE + 16 * ks + 8 * half]);
+                S[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[ks], S[mb], 0, 0, 0);
+            }
+        }
+
+        // ---- causal mask (only tiles that reach past the first row's horizon) -------------------
+        if (kt0 + BN - 1 > wq_min) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = kt0 + 32 * mb + (i >> 2) * 8 + half * 4 + (i & 3);
+                    if (key > qpos) S[mb][i] = -INFINITY;
+                }
+        }
+
+        // ---- online softmax -----------------------------------------------------------------------
+        float mx = S[0][0];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[mb][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = exp2f((m_run - m_new) * cscale);
+        const float mc = m_new * cscale;
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8 Pb[4];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int kk2 = 0; kk2 < 2; ++kk2) {
+                uint32_t pk[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float p0 = exp2f(S[mb][8 * kk2 + 2 * w] * cscale - mc);
+                    const float p1 = exp2f(S[mb][8 * kk2 + 2 * w + 1] * cscale - mc);
+                    psum += p0 + p1;
+                    pk[w] = pack_bf16(p0, p1);
+                }
+                Pb[2 * mb + kk2] = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int db = 0; db < DBLKS; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[db][i] *= alpha;
+
+        // ---- O^T += V^T P^T -------------------------------------------------------------------------
+#pragma unroll
+        for (int db = 0; db < DBLKS; ++db)
+#pragma unroll
+            for (int ks2 = 0; ks2 < 4; ++ks2) {
+                const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(&Vt[(32 * db + lq) * VT_STRIDE + 16 * ks2 + 8 * half]);
+                O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, Pb[ks2], O[db], 0, 0, 0);
+            }
+    }
+
+    // ---- epilogue: normalise and store --------------------------------------------------------------
+    const float l_all = l_run + __shfl_xor(l_run, 32);
+    if (row_valid) {
+        const float inv = 1.f / l_all;
+        uint16_t *orow = a.out + ((int64_t)(q0 + j) * a.n_q_heads + head) * D;
+#pragma unroll
+        for (int db = 0; db < DBLKS; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int d = 32 * db + i4 * 8 + half * 4;
+                uint2 o;
+                o.x = pack_bf16(O[db][4 * i4] * inv, O[db][4 * i4 + 1] * inv);
+                o.y = pack_bf16(O[db][4 * i4 + 2] * inv, O[db][4 * i4 + 3] * inv);
+                *reinterpret_cast<uint2 *>(orow + d) = o;
+            }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t stream) {
+    if (a.n_items <= 0) return hipSuccess;
+    dim3 grid(a.n_items), block(NTHREADS);
+    if (a.head_dim == 128 && a.rope_style == 0)
+        hipLaunchKernelGGL((attn_mfma_kernel<128, 0>), grid, block, 0, stream, a);
+    else if (a.head_dim == 128)
+        hipLaunchKernelGGL((attn_mfma_kernel<128, 1>), grid, block, 0, stream, a);
+    else if (a.head_dim == 64 && a.rope_style == 0)
+        hipLaunchKernelGGL((attn_mfma_kernel<64, 0>), grid, block, 0, stream, a);
+    else if (a.head_dim == 64)
+        hipLaunchKernelGGL((attn_mfma_kernel<64, 1>), grid, block, 0, stream, a);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace ca

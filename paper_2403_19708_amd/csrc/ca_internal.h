@@ -1,0 +1,92 @@
+// Internal declarations shared by the host side of the library and its kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ca {
+
+constexpr int kMaxSeqsPerLaunch = 64;  // per-conversation arguments travel in the kernel-argument block
+constexpr int kPageSize = 16;
+constexpr int kXcds = 8;               // MI355X: 8 accelerator dies, workgroup i runs on die i % 8
+
+// ---------------------------------------------------------------------------------------
+// paged pool <-> contiguous rows (Section 3.2: layer-wise load / save are data movement)
+// ---------------------------------------------------------------------------------------
+// One entry per conversation handled by a launch.  "contig" is [token][n_kv_heads][head_dim];
+// token (contig_tok0 + i) <-> context token (ctx_tok0 + i) for i < count.
+struct MoveArgs {
+    uint8_t *contig_k[kMaxSeqsPerLaunch];
+    uint8_t *contig_v[kMaxSeqsPerLaunch];
+    int64_t contig_tok0[kMaxSeqsPerLaunch];
+    int32_t ctx_tok0[kMaxSeqsPerLaunch];
+    int32_t count[kMaxSeqsPerLaunch];
+    int32_t seq[kMaxSeqsPerLaunch];  // row of the block table
+};
+
+struct MoveShape {
+    const int32_t *block_table;  // device [n_seqs][max_pages]
+    int32_t max_pages;
+    int32_t n_kv_heads;
+    int32_t vecs_per_row;        // head_dim * esize / 16
+    int32_t n_in_launch;
+    int32_t max_count;           // largest count in this launch
+};
+
+// to_pool = true: contiguous -> pages (unpack / append); false: pages -> contiguous (pack).
+hipError_t launch_move(bool to_pool, const MoveArgs &args, const MoveShape &shape, uint8_t *k_pool,
+                       uint8_t *v_pool, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// Section 3.4: per-token metadata of the rebased plan
+// ---------------------------------------------------------------------------------------
+struct RebaseArgs {
+    int32_t n_seqs;
+    int32_t max_pages;
+    const int32_t *block_table;  // device
+    const int32_t *n_keep;       // device [n_seqs]
+    const int32_t *cu_q;         // device [n_seqs+1]
+    const int32_t *cu_k;         // device [n_seqs+1]
+    int32_t *q_pos;              // device [sum new]
+    int32_t *q_seq;              // device [sum new]
+    int32_t *slot_map;           // device [sum context]
+    int32_t total_q, total_k;
+};
+hipError_t launch_rebase(const RebaseArgs &args, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// Sections 2.1 / 3.1 / 3.4: attention of the new tokens over [kept history | new tokens]
+// ---------------------------------------------------------------------------------------
+struct WorkItem {      // one tile of stacked query rows of one (conversation, kv head)
+    int32_t seq;       // -1: padding, the workgroup exits
+    int32_t kv_head;
+    int32_t row0;      // first stacked row; row r <-> new token r / G, query head kv_head*G + r % G
+    int32_t n_rows;
+};
+
+struct AttnArgs {
+    const uint16_t *q;       // bf16 bits
+    uint16_t *out;
+    const uint16_t *k_pool;
+    const uint16_t *v_pool;
+    const int32_t *block_table;
+    const int32_t *n_keep;
+    const int32_t *cu_q;
+    const int32_t *q_pos;    // [total_q] rebased position of every new token
+    const int32_t *q_seq;    // [total_q] its conversation
+    const WorkItem *items;
+    const float2 *rope;      // [max_positions][head_dim/2] (cos, sin)
+    int32_t n_items;
+    int32_t total_q;
+    int32_t max_pages;
+    int32_t n_q_heads, n_kv_heads, head_dim;
+    int32_t rope_style;
+    float softmax_scale;
+};
+
+constexpr int kAttnTileRowsMfma = 128;  // 4 wavefronts x 32 stacked query rows
+
+hipError_t launch_attn_mfma(const AttnArgs &args, hipStream_t stream);
+hipError_t launch_attn_ref(const AttnArgs &args, hipStream_t stream);
+
+}  // namespace ca

@@ -1,0 +1,128 @@
+// Data-movement kernels of the layer-wise load / save path (Section 3.2) and the per-token
+// metadata of the rebased plan (Section 3.4).  Pure integer indexing and 16-byte copies:
+// results are bit-exact by construction.
+//
+// HBM-bound.  Per token and layer the kernels move n_kv_heads*head_dim*2 bytes of K and as many
+// of V, read once and written once.  A workgroup owns 16 consecutive context tokens of one
+// conversation; for a fixed head its 256 lanes cover 16 tokens x 256 B, which is one whole
+// (page, head) block of the pool (4 KiB contiguous) on the paged side and 16 rows of 256 B on
+// the contiguous side, so both sides move in full 256-byte segments.
+#include "ca_internal.h"
+
+namespace ca {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int vec16;  // one 16-byte piece
+
+constexpr int kMoveThreads = 256;
+constexpr int kMoveToks = 16;
+constexpr int kUnroll = 4;
+
+template <bool kToPool>
+__global__ __launch_bounds__(kMoveThreads) void move_kernel(MoveArgs a, MoveShape s,
+                                                            uint8_t *__restrict__ k_pool,
+                                                            uint8_t *__restrict__ v_pool) {
+    const int e = blockIdx.y;  // entry of this launch
+    const int count = a.count[e];
+    const int tok_first = blockIdx.x * kMoveToks;
+    if (tok_first >= count) return;
+    const int n_tok = min(kMoveToks, count - tok_first);
+    const int vpr = s.vecs_per_row;
+    const int H = s.n_kv_heads;
+    const int32_t *table = s.block_table + (int64_t)a.seq[e] * s.max_pages;
+    const int64_t row_vecs = (int64_t)H * vpr;  // 16-byte vectors per token on the contiguous side
+    const vec16 *ck = reinterpret_cast<const vec16 *>(a.contig_k[e]) + (a.contig_tok0[e] + tok_first) * row_vecs;
+    const vec16 *cv = reinterpret_cast<const vec16 *>(a.contig_v[e]) + (a.contig_tok0[e] + tok_first) * row_vecs;
+    vec16 *pk = reinterpret_cast<vec16 *>(k_pool);
+    vec16 *pv = reinterpret_cast<vec16 *>(v_pool);
+    const int ctx0 = a.ctx_tok0[e] + tok_first;
+
+    // vector id v -> (head, token-in-group, 16-byte piece), piece fastest
+    const int per_head = kMoveToks * vpr;
+    const int total = H * per_head;
+    for (int v0 = threadIdx.x; v0 < total; v0 += kMoveThreads * kUnroll) {
+        vec16 rk[kUnroll], rv[kUnroll];
+        int64_t pool_idx[kUnroll], contig_idx[kUnroll];
+        bool live[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int v = v0 + u * kMoveThreads;
+            const int h = v / per_head;
+            const int rem = v - h * per_head;
+            const int ti = rem / vpr;
+            const int piece = rem - ti * vpr;
+            live[u] = (v < total) && (ti < n_tok);
+            const int t = ctx0 + (live[u] ? ti : 0);
+            const int page = table[t / kPageSize];
+            const int slot = t % kPageSize;
+            pool_idx[u] = (((int64_t)page * H + h) * kPageSize + slot) * vpr + piece;
+            contig_idx[u] = (int64_t)ti * row_vecs + (int64_t)h * vpr + piece;
+            if (live[u]) {
+                if (kToPool) {
+                    rk[u] = __builtin_nontemporal_load(ck + contig_idx[u]);
+                    rv[u] = __builtin_nontemporal_load(cv + contig_idx[u]);
+                } else {
+                    rk[u] = __builtin_nontemporal_load(pk + pool_idx[u]);
+                    rv[u] = __builtin_nontemporal_load(pv + pool_idx[u]);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (live[u]) {
+                if (kToPool) {
+                    pk[pool_idx[u]] = rk[u];
+                    pv[pool_idx[u]] = rv[u];
+                } else {
+                    const_cast<vec16 *>(ck)[contig_idx[u]] = rk[u];
+                    const_cast<vec16 *>(cv)[contig_idx[u]] = rv[u];
+                }
+            }
+        }
+    }
+}
+
+// One thread per context token: which conversation it belongs to (binary search in the prefix
+// sums), where it lives in the pool, and for new tokens their rebased position.
+__global__ __launch_bounds__(256) void rebase_kernel(RebaseArgs a) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.total_k) return;
+    int lo = 0, hi = a.n_seqs;  // largest c with cu_k[c] <= i
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (a.cu_k[mid] <= i) lo = mid; else hi = mid;
+    }
+    const int c = lo;
+    const int t = i - a.cu_k[c];
+    const int page = a.block_table[(int64_t)c * a.max_pages + t / kPageSize];
+    a.slot_map[i] = page * kPageSize + t % kPageSize;
+    const int n = a.n_keep[c];
+    if (t >= n) {
+        const int j = t - n;
+        a.q_pos[a.cu_q[c] + j] = t;  // new token j sits at position n + j of the truncated context
+        a.q_seq[a.cu_q[c] + j] = c;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_move(bool to_pool, const MoveArgs &args, const MoveShape &shape, uint8_t *k_pool,
+                       uint8_t *v_pool, hipStream_t stream) {
+    if (shape.n_in_launch <= 0 || shape.max_count <= 0) return hipSuccess;
+    dim3 grid((shape.max_count + kMoveToks - 1) / kMoveToks, shape.n_in_launch);
+    if (to_pool)
+        hipLaunchKernelGGL(move_kernel<true>, grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);
+    else
+        hipLaunchKernelGGL(move_kernel<false>, grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);
+    return hipGetLastError();
+}
+
+hipError_t launch_rebase(const RebaseArgs &args, hipStream_t stream) {
+    if (args.total_k <= 0) return hipSuccess;
+    dim3 grid((args.total_k + 255) / 256);
+    hipLaunchKernelGGL(rebase_kernel, grid, dim3(256), 0, stream, args);
+    return hipGetLastError();
+}
+
+}  // namespace ca

@@ -1,0 +1,134 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, validates configurations and batches, and its truncation planner agrees with
+the oracle's bit for bit.  No compute entry point is called here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2403_19708_amd as ca
+from paper_2403_19708_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ca.lib_path()):
+        from paper_2403_19708_amd import build
+        build.build(verbose=False)
+    return ca.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ca.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ca_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_symbols()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.SYMBOLS) == names          # the binding covers the whole header
+
+
+def test_status_strings(lib):
+    for code, name in binding.STATUS.items():
+        assert lib.ca_status_string(code).decode() == name
+
+
+def test_config_default_and_struct_layout(lib):
+    c = binding._CConfig()
+    lib.ca_config_default(ctypes.byref(c))
+    assert (c.page_size, c.head_dim, c.rope_style, c.pipeline_depth) == (16, 128, 0, 2)
+    assert abs(c.rope_base - 10000.0) < 1e-3 and c.require_load == 1
+    ca.config_validate(ca.Config())
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(head_dim=96), "CA_ERR_UNSUPPORTED"),
+    (dict(page_size=32), "CA_ERR_UNSUPPORTED"),
+    (dict(rope_style=2), "CA_ERR_UNSUPPORTED"),
+    (dict(n_q_heads=6, n_kv_heads=4), "CA_ERR_INVALID_ARG"),
+    (dict(n_layers=0), "CA_ERR_INVALID_ARG"),
+    (dict(rope_base=0.5), "CA_ERR_INVALID_ARG"),
+    (dict(pipeline_depth=0), "CA_ERR_OUT_OF_RANGE"),
+    (dict(max_positions=0), "CA_ERR_OUT_OF_RANGE"),
+    (dict(max_batch_q_tokens=1 << 20, max_batch_kv_tokens=1 << 10), "CA_ERR_OUT_OF_RANGE"),
+    (dict(attn_variant=7), "CA_ERR_INVALID_ARG"),
+])
+def test_config_validation(lib, kw, status):
+    with pytest.raises(ca.CaError) as e:
+        ca.config_validate(ca.Config(**kw))
+    assert e.value.status_name == status
+
+
+def _good_batch():
+    hist = np.array([40, 0, 100], np.int32)
+    keep = np.array([8, 0, 100], np.int32)
+    new = np.array([5, 17, 3], np.int32)
+    bt = np.array([[3, 7, 1, 0], [2, 9, 0, 0], [4, 0, 0, 0]], np.int32)   # needs 3, 2, 1 pages
+    return hist, keep, new, bt, 10
+
+
+def test_batch_validation_accepts_a_good_batch(lib):
+    ca.batch_validate(ca.Config(max_positions=128), *_good_batch())
+
+
+@pytest.mark.parametrize("mutate,status", [
+    (lambda h, k, n, bt, p: (h, np.array([41, 0, 100], np.int32), n, bt, p), "CA_ERR_OUT_OF_RANGE"),   # keep_start > hist
+    (lambda h, k, n, bt, p: (h, np.array([-1, 0, 100], np.int32), n, bt, p), "CA_ERR_OUT_OF_RANGE"),
+    (lambda h, k, n, bt, p: (h, k, np.array([5, 0, 3], np.int32), bt, p), "CA_ERR_INVALID_ARG"),      # empty turn
+    (lambda h, k, n, bt, p: (h, k, n, np.where(bt == 9, 10, bt).astype(np.int32), p), "CA_ERR_OUT_OF_RANGE"),  # page id
+    (lambda h, k, n, bt, p: (h, k, n, np.where(bt == 9, -1, bt).astype(np.int32), p), "CA_ERR_OUT_OF_RANGE"),
+    (lambda h, k, n, bt, p: (h, k, n, np.where(bt == 9, 3, bt).astype(np.int32), p), "CA_ERR_INVALID_ARG"),    # shared page
+    (lambda h, k, n, bt, p: (h, k, n, bt[:, :2].copy(), p), "CA_ERR_OUT_OF_RANGE"),                   # too few columns
+    (lambda h, k, n, bt, p: (np.array([400, 0, 100], np.int32), k, n, bt, p), "CA_ERR_OUT_OF_RANGE"),  # beyond window
+])
+def test_batch_validation_rejects(lib, mutate, status):
+    with pytest.raises(ca.CaError) as e:
+        ca.batch_validate(ca.Config(max_positions=128), *mutate(*_good_batch()))
+    assert e.value.status_name == status
+
+
+def test_batch_validation_limits(lib):
+    h, k, n, bt, p = _good_batch()
+    with pytest.raises(ca.CaError) as e:
+        ca.batch_validate(ca.Config(max_positions=128, max_seqs=2), h, k, n, bt, p)
+    assert e.value.status_name == "CA_ERR_OUT_OF_RANGE"
+    with pytest.raises(ca.CaError) as e:
+        ca.batch_validate(ca.Config(max_positions=128, max_batch_kv_tokens=40, max_batch_q_tokens=30), h, k, n, bt, p)
+    assert e.value.status_name == "CA_ERR_OUT_OF_RANGE"
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2])
+def test_planner_agrees_with_oracle_bit_for_bit(lib, policy):
+    rng = np.random.default_rng(100 + policy)
+    for W, r in ((4096, 0.5), (2048, 0.5), (97, 0.3), (64, 0.75), (4096, 0.1)):
+        h = rng.integers(0, 3 * W, 500).astype(np.int32)
+        n = rng.integers(0, W, 500).astype(np.int32)
+        assert np.array_equal(ca.truncate_plan(h, n, W, r, policy), oracle.truncate_plan(h, n, W, r, policy))
+
+
+def test_planner_rejects_bad_arguments(lib):
+    for kw in (dict(window=0), dict(ratio=0.0), dict(ratio=1.0), dict(policy=3)):
+        args = dict(window=16, ratio=0.5, policy=0)
+        args.update(kw)
+        with pytest.raises(ca.CaError):
+            ca.truncate_plan([10], [10], **args)
+    with pytest.raises(ca.CaError):
+        ca.truncate_plan([-1], [10], 16)
+
+
+def test_create_without_gpu_fails_cleanly(lib):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(ca.CaError) as e:
+        ca.Context(ca.Config())
+    assert e.value.status_name in ("CA_ERR_HIP", "CA_ERR_OUT_OF_RANGE")
