@@ -79,6 +79,8 @@ typedef struct {
                              /* then unpack; 2: the unpack kernel reads the source in place   */
                              /* (source must be device-accessible)                            */
     int32_t attn_variant;    /* 0: MFMA kernel; 1: scalar fp32 kernel (slow, for checking)    */
+    int32_t attn_tile_rows;  /* stacked query rows per workgroup of the MFMA kernel: 128, 256,  */
+                             /* or 0 = choose per batch                                        */
     int32_t require_load;    /* 1: attention on a layer with kept history that was not loaded */
                              /* under the current plan fails with CA_ERR_NOT_READY            */
     int32_t device;          /* HIP device ordinal                                            */

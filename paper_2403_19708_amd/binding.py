@@ -39,7 +39,8 @@ class _CConfig(C.Structure):
                 ("rope_base", C.c_float), ("rope_style", C.c_int32), ("pipeline_depth", C.c_int32),
                 ("max_seqs", C.c_int32), ("max_batch_kv_tokens", C.c_int64),
                 ("max_batch_q_tokens", C.c_int64), ("load_mode", C.c_int32),
-                ("attn_variant", C.c_int32), ("require_load", C.c_int32), ("device", C.c_int32)]
+                ("attn_variant", C.c_int32), ("attn_tile_rows", C.c_int32), ("require_load", C.c_int32),
+                ("device", C.c_int32)]
 
 
 class _CBatch(C.Structure):
@@ -119,6 +120,7 @@ class Config:
     max_batch_q_tokens: int = 1 << 14
     load_mode: int = 0
     attn_variant: int = 0
+    attn_tile_rows: int = 0
     require_load: int = 1
     device: int = 0
 

@@ -81,10 +81,12 @@ struct AttnArgs {
     int32_t max_pages;
     int32_t n_q_heads, n_kv_heads, head_dim;
     int32_t rope_style;
+    int32_t tile_rows;       // stacked query rows per workgroup: 128 (4 wavefronts) or 256 (8)
     float softmax_scale;
 };
 
-constexpr int kAttnTileRowsMfma = 128;  // 4 wavefronts x 32 stacked query rows
+constexpr int kAttnTileRowsMin = 128;   // smallest tile of stacked query rows (4 wavefronts x 32)
+constexpr int kRopeMinRows = 256;       // the kernels read table rows below this whatever the window
 
 hipError_t launch_attn_mfma(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_ref(const AttnArgs &args, hipStream_t stream);

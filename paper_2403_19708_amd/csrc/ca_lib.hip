@@ -38,7 +38,7 @@ struct ca_ctx {
            off_q_seq = 0, off_slot_map = 0, upload_bytes = 0;
     // current plan (host copies)
     bool has_plan = false;
-    int32_t n_seqs = 0, max_pages = 0, num_pages = 0, n_items = 0;
+    int32_t n_seqs = 0, max_pages = 0, num_pages = 0, n_items = 0, tile_rows = 128;
     int64_t total_q = 0, total_k = 0, total_n = 0;
     std::vector<int32_t> hist_len, keep_start, new_len, n_keep, cu_q, cu_k;
     std::vector<int64_t> cu_n;
@@ -180,6 +180,7 @@ void ca_config_default(ca_config *c) {
     c->max_batch_q_tokens = 1 << 14;
     c->load_mode = 0;
     c->attn_variant = 0;
+    c->attn_tile_rows = 0;
     c->require_load = 1;
     c->device = 0;
 }
@@ -230,6 +231,10 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
     if (c->load_mode < 0 || c->load_mode > 2 || c->attn_variant < 0 || c->attn_variant > 1) {
         set_err(err, err_len, "load_mode (0..2) or attn_variant (0..1) out of range");
         return CA_ERR_INVALID_ARG;
+    }
+    if (c->attn_tile_rows != 0 && c->attn_tile_rows != 128 && c->attn_tile_rows != 256) {
+        set_err(err, err_len, "attn_tile_rows %d unsupported (0, 128 or 256)", c->attn_tile_rows);
+        return CA_ERR_UNSUPPORTED;
     }
     if (c->device < 0) { set_err(err, err_len, "device < 0"); return CA_ERR_INVALID_ARG; }
     return CA_OK;
@@ -393,11 +398,12 @@ static ca_status create_impl(ca_ctx *ctx) {
     // Rotary table (Section 3.4): cos/sin of pos * base^(-2i/D), evaluated in fp64, stored fp32.
     {
         const int half = c.head_dim / 2;
-        std::vector<float2> tab((size_t)c.max_positions * half);
+        const int rows = std::max(c.max_positions, kRopeMinRows);
+        std::vector<float2> tab((size_t)rows * half);
         std::vector<double> inv_freq(half);
         for (int i = 0; i < half; ++i)
             inv_freq[i] = std::exp(-std::log((double)c.rope_base) * (2.0 * i) / (double)c.head_dim);
-        for (int p = 0; p < c.max_positions; ++p)
+        for (int p = 0; p < rows; ++p)
             for (int i = 0; i < half; ++i) {
                 const double ang = (double)p * inv_freq[i];
                 tab[(size_t)p * half + i] = make_float2((float)std::cos(ang), (float)std::sin(ang));
@@ -413,7 +419,7 @@ static ca_status create_impl(ca_ctx *ctx) {
         const size_t units = (size_t)c.max_seqs * c.n_kv_heads;
         const size_t g = (size_t)c.n_q_heads / c.n_kv_heads;
         // tiles: sum over units of ceil(rows/tile) <= total_q*g*n_kv_heads/tile + units, padded per die
-        const size_t max_items = (size_t)c.max_batch_q_tokens * g * c.n_kv_heads / kAttnTileRowsMfma + units;
+        const size_t max_items = (size_t)c.max_batch_q_tokens * g * c.n_kv_heads / kAttnTileRowsMin + units;
         const size_t max_items_padded = (max_items + 1) * kXcds;  // worst case: every tile on one die
         size_t off = 0;
         ctx->off_table = off;   off = align_up(off + (size_t)c.max_seqs * max_cols * 4, 256);
@@ -531,7 +537,15 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
     // Units go longest-first to the least loaded die; dies are padded to equal length.
     {
         const int G = c.n_q_heads / c.n_kv_heads;
-        const int tile = kAttnTileRowsMfma;
+        // 256-row tiles (8 wavefronts) halve the K/V re-reads and the rotary work per row when a
+        // (conversation, kv head) has more than 128 stacked rows; small turns keep 128-row tiles
+        int tile = c.attn_tile_rows;
+        if (tile == 0) {
+            int most = 0;
+            for (int i = 0; i < B; ++i) most = std::max(most, b->new_len[i] * G);
+            tile = most > 128 ? 256 : 128;
+        }
+        ctx->tile_rows = tile;
         struct Unit { int32_t seq, head; int64_t work; };
         std::vector<Unit> units;
         units.reserve((size_t)B * c.n_kv_heads);
@@ -924,6 +938,7 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
     a.n_kv_heads = c.n_kv_heads;
     a.head_dim = c.head_dim;
     a.rope_style = c.rope_style;
+    a.tile_rows = ctx->tile_rows;
     a.softmax_scale = softmax_scale;
     int iv;
     CA_HIP(ctx, prof_begin(ctx, kProfAttn, stream, &iv));
