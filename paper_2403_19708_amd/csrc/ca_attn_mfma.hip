@@ -199,6 +199,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
 
     uint4 kx[KT], ky[KT], vv[4];
 
+    // Page ids are looked up one tile ahead of the loads that need them, so that the dependent
+    // chain  block table -> page -> K/V row  never stalls a load: k_page[u] / v_page hold the pages of
+    // the tile that the NEXT fetch_k / fetch_v call will read.  Columns past a conversation's last
+    // page repeat a valid page of that row, so reading up to max_pages-1 is always in bounds.
+    const int last_col = a.max_pages - 1;
+    int k_page[KT], v_page;
+#pragma unroll
+    for (int u = 0; u < KT; ++u) k_page[u] = table[min(((tid + u * NTHREADS) / PIECES) >> 4, last_col)];
+    v_page = table[min((4 * v_kq) >> 4, last_col)];
+
     // GUARD = false: the tile is known to lie entirely inside the visible keys (no bounds checks)
     auto fetch_k = [&](int tile, auto guard_tag) {   // HBM -> registers
         constexpr bool GUARD = decltype(guard_tag)::value;
@@ -211,12 +221,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
                 kx[u] = make_uint4(0, 0, 0, 0);
                 ky[u] = make_uint4(0, 0, 0, 0);
             }
-            if (task < K_TASKS && (!GUARD || t < kmax)) {
-                const int page = table[t >> 4];
-                const uint16_t *krow = a.k_pool + (((int64_t)page * Hkv + g) * kPageSize + (t & 15)) * D;
+            if ((K_TASKS % NTHREADS == 0 || task < K_TASKS) && (!GUARD || t < kmax)) {
+                const uint16_t *krow = a.k_pool + (((int64_t)k_page[u] * Hkv + g) * kPageSize + (t & 15)) * D;
                 kx[u] = *reinterpret_cast<const uint4 *>(krow + 8 * k_piece);
                 ky[u] = *reinterpret_cast<const uint4 *>(krow + HALF + 8 * k_piece);
             }
+            k_page[u] = table[min((t + BN) >> 4, last_col)];
         }
     };
 
@@ -226,33 +236,55 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
         if (v_active) {
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                const int t = kt0 + 4 * v_kq + rr;
+                const int t = kt0 + 4 * v_kq + rr;   // the 4 keys of a quad share a page
                 if (GUARD) vv[rr] = make_uint4(0, 0, 0, 0);
                 if (!GUARD || t < kmax) {
-                    const int page = table[t >> 4];
-                    const uint16_t *vrow = a.v_pool + (((int64_t)page * Hkv + g) * kPageSize + (t & 15)) * D;
+                    const uint16_t *vrow = a.v_pool + (((int64_t)v_page * Hkv + g) * kPageSize + (t & 15)) * D;
                     vv[rr] = *reinterpret_cast<const uint4 *>(vrow + 8 * v_dc);
+                }
+            }
+            v_page = table[min((kt0 + BN + 4 * v_kq) >> 4, last_col)];
+        }
+    };
+
+    // registers -> rotate -> LDS, then advance the rotation by one tile.  Cut into 4 parts (one per
+    // dword of the two 16-byte pieces) so that the caller can spread the arithmetic between the
+    // matrix instructions of the S^T product.
+    auto stage_k_part = [&](int buf, int w) {
+#pragma unroll
+        for (int u = 0; u < KT; ++u) {
+            const int task = tid + u * NTHREADS;
+            if (K_TASKS % NTHREADS == 0 || task < K_TASKS) {
+                uint32_t *pa = reinterpret_cast<uint32_t *>(&kx[u]);
+                uint32_t *pb = reinterpret_cast<uint32_t *>(&ky[u]);
+                const float a0 = bf_lo(pa[w]), a1 = bf_hi(pa[w]);
+                const float b0 = bf_lo(pb[w]), b1 = bf_hi(pb[w]);
+                if (STYLE == 0) {
+                    const float2 c0 = k_cs[u][2 * w], c1 = k_cs[u][2 * w + 1];
+                    pa[w] = pack_bf16(a0 * c0.x - b0 * c0.y, a1 * c1.x - b1 * c1.y);
+                    pb[w] = pack_bf16(b0 * c0.x + a0 * c0.y, b1 * c1.x + a1 * c1.y);
+                } else {
+                    const float2 ca_ = k_cs[u][w], cb_ = k_cs[u][4 + w];
+                    pa[w] = pack_bf16(a0 * ca_.x - a1 * ca_.y, a1 * ca_.x + a0 * ca_.y);
+                    pb[w] = pack_bf16(b0 * cb_.x - b1 * cb_.y, b1 * cb_.x + b0 * cb_.y);
+                }
+#pragma unroll
+                for (int e2 = 0; e2 < 2; ++e2) {
+                    const int e = (STYLE == 0) ? 2 * w + e2 : w + 4 * e2;
+                    const float2 o = k_cs[u][e], st = k_step[e];
+                    k_cs[u][e] = make_float2(o.x * st.x - o.y * st.y, o.y * st.x + o.x * st.y);
+                }
+                if (w == 3) {
+                    const int kk = task / PIECES;
+                    *reinterpret_cast<uint4 *>(&Ks[buf][kk * KS_STRIDE + 8 * k_piece]) = kx[u];
+                    *reinterpret_cast<uint4 *>(&Ks[buf][kk * KS_STRIDE + HALF + 8 * k_piece]) = ky[u];
                 }
             }
         }
     };
-
-    auto stage_k = [&](int buf) {  // registers -> rotate -> LDS, then advance the rotation by one tile
+    auto stage_k = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < KT; ++u) {
-            const int task = tid + u * NTHREADS;
-            if (task < K_TASKS) {
-                rotate16<STYLE>(kx[u], ky[u], k_cs[u]);
-                const int kk = task / PIECES;
-                *reinterpret_cast<uint4 *>(&Ks[buf][kk * KS_STRIDE + 8 * k_piece]) = kx[u];
-                *reinterpret_cast<uint4 *>(&Ks[buf][kk * KS_STRIDE + HALF + 8 * k_piece]) = ky[u];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float2 o = k_cs[u][e], s = k_step[e];
-                    k_cs[u][e] = make_float2(o.x * s.x - o.y * s.y, o.y * s.x + o.x * s.y);
-                }
-            }
-        }
+        for (int w = 0; w < 4; ++w) stage_k_part(buf, w);
     };
 
     auto stage_v = [&](int buf) {  // registers -> 4x8 transpose -> LDS as V^T
@@ -298,26 +330,42 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
         const bool compute = LIVE && (INTERIOR || kt0 <= wq_max);   // anything visible to this wavefront?
 
         f32x16 S[2];
-        if (compute) {
-            // ---- S^T = K Q^T ----------------------------------------------------------------------
+        if (INTERIOR && LIVE) {
+            // ---- S^T = K Q^T, with the staging of the next K tile spread between the matrix instructions --
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) S[mb][i] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks)
+            for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb) {
                     const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&Ks[buf][(32 * mb + lq) * KS_STRIDE + 16 * ks + 8 * half]);
                     S[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[ks], S[mb], 0, 0, 0);
                 }
+                if (ks % (KSTEPS / 4) == KSTEPS / 4 - 1) stage_k_part(buf ^ 1, ks / (KSTEPS / 4));
+            }
+            fetch_k(tile + 2, std::false_type{});
+        } else {
+            if (compute) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) S[mb][i] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) {
+                        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(&Ks[buf][(32 * mb + lq) * KS_STRIDE + 16 * ks + 8 * half]);
+                        S[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[ks], S[mb], 0, 0, 0);
+                    }
+            }
+            // ---- producer: tile+1 from registers into the other LDS buffer (free since the last barrier),
+            // and, the registers being free again, the loads of tile+2 start a whole tile ahead of their use
+            if (INTERIOR || tile + 1 < n_tiles) stage_k(buf ^ 1);
+            if (INTERIOR) fetch_k(tile + 2, std::false_type{});
+            else if (tile + 2 < n_tiles) fetch_k(tile + 2, std::true_type{});
         }
-
-        // ---- producer: tile+1 from registers into the other LDS buffer (free since the last barrier),
-        // and, the registers being free again, the loads of tile+2 start a whole tile ahead of their use
-        if (INTERIOR || tile + 1 < n_tiles) stage_k(buf ^ 1);
-        if (INTERIOR) fetch_k(tile + 2, std::false_type{});
-        else if (tile + 2 < n_tiles) fetch_k(tile + 2, std::true_type{});
 
         if (compute) {
             // ---- causal mask (only tiles that reach past the first row's horizon) -------------------
