@@ -48,6 +48,7 @@ def parse():
     ap.add_argument("--pipeline-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
+    ap.add_argument("--load-mode", type=int, default=0, help="library load_mode for the pinned-host leg (0 staged copies, 2 kernels access the host tier in place)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging only; marks the result invalid)")
     return ap.parse_args()
 
@@ -144,7 +145,7 @@ def main():
         base, esz = bufs[layer].data_ptr(), row * 2
         return [base + int(tier_off[c]) * esz for c in range(B)]
 
-    conf = ca.Config(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=W,
+    conf = ca.Config(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=W, load_mode=args.load_mode,
                      pipeline_depth=2, max_seqs=B, max_batch_kv_tokens=tot_k + 64, max_batch_q_tokens=tot_q + 16)
     ctx = ca.Context(conf)
     stream = torch.cuda.current_stream()

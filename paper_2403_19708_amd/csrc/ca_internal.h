@@ -29,8 +29,9 @@ struct MoveShape {
     int32_t max_pages;
     int32_t n_kv_heads;
     int32_t vecs_per_row;        // head_dim * esize / 16
+    int32_t heads_per_wg;        // heads one workgroup moves (grid.z slices the heads)
     int32_t n_in_launch;
-    int32_t max_count;           // largest count in this launch
+    int32_t max_pages_touched;   // largest number of pages a range of this launch touches
 };
 
 // to_pool = true: contiguous -> pages (unpack / append); false: pages -> contiguous (pack).

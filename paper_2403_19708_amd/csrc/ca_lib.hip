@@ -663,11 +663,13 @@ ca_status run_move(ca_ctx *ctx, bool to_pool, const std::vector<Segment> &segs, 
     shape.max_pages = ctx->max_pages;
     shape.n_kv_heads = c.n_kv_heads;
     shape.vecs_per_row = c.head_dim * 2 / 16;
+    // one 256-lane pass of 4 x 16 bytes per lane and array covers 16 tokens x 16 KiB / (16 * row piece)
+    shape.heads_per_wg = std::max(1, std::min(c.n_kv_heads, 4 * 256 / (16 * shape.vecs_per_row)));
     for (size_t at = 0; at < segs.size(); at += kMaxSeqsPerLaunch) {
         MoveArgs args;
         std::memset(&args, 0, sizeof args);
         const int n = (int)std::min<size_t>(kMaxSeqsPerLaunch, segs.size() - at);
-        int max_count = 0;
+        int max_touched = 0;
         for (int i = 0; i < n; ++i) {
             const Segment &s = segs[at + i];
             args.contig_k[i] = s.k;
@@ -676,10 +678,11 @@ ca_status run_move(ca_ctx *ctx, bool to_pool, const std::vector<Segment> &segs, 
             args.ctx_tok0[i] = s.ctx_tok0;
             args.count[i] = s.count;
             args.seq[i] = s.seq;
-            max_count = std::max(max_count, s.count);
+            if (s.count > 0)
+                max_touched = std::max(max_touched, (s.ctx_tok0 + s.count - 1) / kPageSize - s.ctx_tok0 / kPageSize + 1);
         }
         shape.n_in_launch = n;
-        shape.max_count = max_count;
+        shape.max_pages_touched = max_touched;
         CA_HIP(ctx, launch_move(to_pool, args, shape, (uint8_t *)k_pool, (uint8_t *)v_pool, stream));
     }
     return CA_OK;

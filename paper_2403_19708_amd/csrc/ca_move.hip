@@ -16,55 +16,64 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) unsigned int vec16;  // one 16-byte piece
 
 constexpr int kMoveThreads = 256;
-constexpr int kMoveToks = 16;
 constexpr int kUnroll = 4;
 
-template <bool kToPool>
+// grid: x = page of the conversation's context (counted from the first page the range touches),
+// y = conversation entry of this launch, z = slice of heads.  A workgroup moves the tokens of its
+// page that lie inside the range, for heads_per_wg heads, K and V: 4 + 4 loads of 16 bytes in
+// flight per lane before the first store.  The page id is uniform over the workgroup.
+template <bool kToPool, bool kNT>
 __global__ __launch_bounds__(kMoveThreads) void move_kernel(MoveArgs a, MoveShape s,
                                                             uint8_t *__restrict__ k_pool,
                                                             uint8_t *__restrict__ v_pool) {
     const int e = blockIdx.y;  // entry of this launch
-    const int count = a.count[e];
-    const int tok_first = blockIdx.x * kMoveToks;
-    if (tok_first >= count) return;
-    const int n_tok = min(kMoveToks, count - tok_first);
+    const int ctx_begin = a.ctx_tok0[e];
+    const int ctx_end = ctx_begin + a.count[e];
+    const int page_col = ctx_begin / kPageSize + blockIdx.x;
+    const int t_first = max(ctx_begin, page_col * kPageSize);
+    const int t_last = min(ctx_end, (page_col + 1) * kPageSize);   // exclusive
+    if (t_first >= t_last) return;
+    const int slot0 = t_first - page_col * kPageSize;
+    const int n_tok = t_last - t_first;
     const int vpr = s.vecs_per_row;
     const int H = s.n_kv_heads;
-    const int32_t *table = s.block_table + (int64_t)a.seq[e] * s.max_pages;
+    const int h_first = blockIdx.z * s.heads_per_wg;
+    const int h_count = min(s.heads_per_wg, H - h_first);
+    const int page = s.block_table[(int64_t)a.seq[e] * s.max_pages + page_col];
     const int64_t row_vecs = (int64_t)H * vpr;  // 16-byte vectors per token on the contiguous side
-    const vec16 *ck = reinterpret_cast<const vec16 *>(a.contig_k[e]) + (a.contig_tok0[e] + tok_first) * row_vecs;
-    const vec16 *cv = reinterpret_cast<const vec16 *>(a.contig_v[e]) + (a.contig_tok0[e] + tok_first) * row_vecs;
-    vec16 *pk = reinterpret_cast<vec16 *>(k_pool);
-    vec16 *pv = reinterpret_cast<vec16 *>(v_pool);
-    const int ctx0 = a.ctx_tok0[e] + tok_first;
+    const int64_t contig_first = a.contig_tok0[e] + (t_first - ctx_begin);
+    const vec16 *ck = reinterpret_cast<const vec16 *>(a.contig_k[e]) + contig_first * row_vecs + (int64_t)h_first * vpr;
+    const vec16 *cv = reinterpret_cast<const vec16 *>(a.contig_v[e]) + contig_first * row_vecs + (int64_t)h_first * vpr;
+    const int64_t pool_first = (((int64_t)page * H + h_first) * kPageSize + slot0) * vpr;
+    vec16 *pk = reinterpret_cast<vec16 *>(k_pool) + pool_first;
+    vec16 *pv = reinterpret_cast<vec16 *>(v_pool) + pool_first;
 
-    // vector id v -> (head, token-in-group, 16-byte piece), piece fastest
-    const int per_head = kMoveToks * vpr;
-    const int total = H * per_head;
+    // vector id v -> (head, token, 16-byte piece), piece fastest
+    const int per_head = n_tok * vpr;
+    const int total = h_count * per_head;
+    const int head_stride_pool = kPageSize * vpr;
     for (int v0 = threadIdx.x; v0 < total; v0 += kMoveThreads * kUnroll) {
         vec16 rk[kUnroll], rv[kUnroll];
-        int64_t pool_idx[kUnroll], contig_idx[kUnroll];
+        int pool_idx[kUnroll];
+        int64_t contig_idx[kUnroll];
         bool live[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int v = v0 + u * kMoveThreads;
-            const int h = v / per_head;
-            const int rem = v - h * per_head;
+            const int hl = v / per_head;
+            const int rem = v - hl * per_head;
             const int ti = rem / vpr;
             const int piece = rem - ti * vpr;
-            live[u] = (v < total) && (ti < n_tok);
-            const int t = ctx0 + (live[u] ? ti : 0);
-            const int page = table[t / kPageSize];
-            const int slot = t % kPageSize;
-            pool_idx[u] = (((int64_t)page * H + h) * kPageSize + slot) * vpr + piece;
-            contig_idx[u] = (int64_t)ti * row_vecs + (int64_t)h * vpr + piece;
+            live[u] = v < total;
+            pool_idx[u] = hl * head_stride_pool + ti * vpr + piece;
+            contig_idx[u] = (int64_t)ti * row_vecs + hl * vpr + piece;
             if (live[u]) {
                 if (kToPool) {
-                    rk[u] = __builtin_nontemporal_load(ck + contig_idx[u]);
-                    rv[u] = __builtin_nontemporal_load(cv + contig_idx[u]);
+                    rk[u] = kNT ? __builtin_nontemporal_load(ck + contig_idx[u]) : ck[contig_idx[u]];
+                    rv[u] = kNT ? __builtin_nontemporal_load(cv + contig_idx[u]) : cv[contig_idx[u]];
                 } else {
-                    rk[u] = __builtin_nontemporal_load(pk + pool_idx[u]);
-                    rv[u] = __builtin_nontemporal_load(pv + pool_idx[u]);
+                    rk[u] = kNT ? __builtin_nontemporal_load(pk + pool_idx[u]) : pk[pool_idx[u]];
+                    rv[u] = kNT ? __builtin_nontemporal_load(pv + pool_idx[u]) : pv[pool_idx[u]];
                 }
             }
         }
@@ -72,11 +81,11 @@ __global__ __launch_bounds__(kMoveThreads) void move_kernel(MoveArgs a, MoveShap
         for (int u = 0; u < kUnroll; ++u) {
             if (live[u]) {
                 if (kToPool) {
-                    pk[pool_idx[u]] = rk[u];
-                    pv[pool_idx[u]] = rv[u];
+                    if (kNT) __builtin_nontemporal_store(rk[u], pk + pool_idx[u]); else pk[pool_idx[u]] = rk[u];
+                    if (kNT) __builtin_nontemporal_store(rv[u], pv + pool_idx[u]); else pv[pool_idx[u]] = rv[u];
                 } else {
-                    const_cast<vec16 *>(ck)[contig_idx[u]] = rk[u];
-                    const_cast<vec16 *>(cv)[contig_idx[u]] = rv[u];
+                    if (kNT) __builtin_nontemporal_store(rk[u], const_cast<vec16 *>(ck) + contig_idx[u]); else const_cast<vec16 *>(ck)[contig_idx[u]] = rk[u];
+                    if (kNT) __builtin_nontemporal_store(rv[u], const_cast<vec16 *>(cv) + contig_idx[u]); else const_cast<vec16 *>(cv)[contig_idx[u]] = rv[u];
                 }
             }
         }
@@ -109,12 +118,14 @@ __global__ __launch_bounds__(256) void rebase_kernel(RebaseArgs a) {
 
 hipError_t launch_move(bool to_pool, const MoveArgs &args, const MoveShape &shape, uint8_t *k_pool,
                        uint8_t *v_pool, hipStream_t stream) {
-    if (shape.n_in_launch <= 0 || shape.max_count <= 0) return hipSuccess;
-    dim3 grid((shape.max_count + kMoveToks - 1) / kMoveToks, shape.n_in_launch);
+    if (shape.n_in_launch <= 0 || shape.max_pages_touched <= 0) return hipSuccess;
+    const int slices = (shape.n_kv_heads + shape.heads_per_wg - 1) / shape.heads_per_wg;
+    dim3 grid(shape.max_pages_touched, shape.n_in_launch, slices);
+    // nontemporal accesses: every byte is touched once (measured ~5 % faster than cached ones)
     if (to_pool)
-        hipLaunchKernelGGL(move_kernel<true>, grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);
+        hipLaunchKernelGGL((move_kernel<true, true>), grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);
     else
-        hipLaunchKernelGGL(move_kernel<false>, grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);
+        hipLaunchKernelGGL((move_kernel<false, true>), grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);
     return hipGetLastError();
 }
 
