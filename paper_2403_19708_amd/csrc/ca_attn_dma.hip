@@ -1,0 +1,433 @@
+// Fused rotary-on-load + causal varlen prefill attention (Sections 2.1, 3.1, 3.4), variant whose
+// K/V tiles travel HBM -> LDS without passing through registers.
+//
+// Same mathematics, work decomposition (8 wavefronts x 32 stacked query rows, key tiles of 64) and
+// matrix-core formulation (S^T = K Q^T, O^T += V^T P^T with v_mfma_f32_32x32x16_bf16) as
+// ca_attn_mfma.hip.  What differs is the memory pipeline:
+//
+//   * global_load_lds (16 bytes per lane, written to LDS at base + lane*16) fills a ring of 4 tile
+//     stages in LDS; the loads of tile T+3 are issued when tile T starts, so two to three tiles
+//     (64-96 KiB per compute unit) are in flight while one is multiplied, and no vector register
+//     is spent on staging.  The only vector-memory instructions inside the walk are these loads,
+//     so s_waitcnt vmcnt(N) with a constant N releases exactly the tile that is needed next.
+//   * The page ids of the conversation are copied into LDS once; the dependent chain
+//     block table -> page -> row costs an LDS read.
+//   * Since the LDS side of such a load is fixed (lane l -> byte l*16 of a 1 KiB chunk), the layout
+//     is chosen on the global side: a chunk holds KPC = 1024/(2D) keys, piece-major
+//     (slot = piece*KPC + key_in_chunk), chunks padded by KPC*16 bytes.  With it the A-operand reads
+//     of K (32 keys x one 16-byte piece), the in-place rotary pass and the transposing reads of V
+//     are all bank-conflict free, and the offset of a piece is linear in the piece index, so the
+//     per-k-step offsets are instruction immediates.
+//   * K lands in LDS without positions; the workgroup rotates the NEXT tile in place (LDS -> fp32
+//     rotate -> bf16 -> same LDS bytes) while the matrix cores work on the current one.
+//   * V is never transposed by the ALUs: ds_read_b64_tr_b16 hands each lane 4 consecutive keys of
+//     one head dimension, which is exactly the A-operand layout of O^T += V^T P^T (two such reads
+//     per operand, in the key order the C layout of S^T imposes on P^T).
+//   * Keys past the end of the context are not zero-filled (a load cannot write zeros): the source
+//     row is clamped to the last valid key, the causal mask gives those columns probability 0 and
+//     the clamped V rows are finite data, so they contribute exactly nothing.
+#include "ca_internal.h"
+
+#include <type_traits>
+
+namespace ca {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+constexpr int BN = 64;    // keys per tile
+constexpr int NW = 8;     // wavefronts per workgroup
+constexpr int NTHREADS = 64 * NW;
+constexpr int NS = 4;     // LDS stages
+constexpr int kMaxPagesLds = 2048;   // page ids kept in LDS: contexts up to 32768 tokens
+
+__device__ inline float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ inline uint32_t pack_bf16(float a, float b) {
+    bf16x2 v = {(__bf16)a, (__bf16)b};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// 16 bytes per lane, global -> LDS at lds_base + lane*16, no register in between.  Written as inline
+// assembly on purpose: the compiler then knows nothing of the outstanding load and does not guard
+// every later LDS read with s_waitcnt vmcnt(0) (it cannot tell which LDS bytes the load will write);
+// the waits are placed by hand with CA_WAIT_VMCNT, which the in-order completion of these loads
+// makes exact.  lds_base must be wave-uniform.
+__device__ inline void dma16(const void *src, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(src) : "memory", "m0");
+}
+
+__device__ inline uint32_t lds_offset(const void *p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "don't wait")
+#define CA_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+template <int D, int STYLE>
+__device__ inline void load_cs(const float2 *__restrict__ rope, int pos, int piece, float2 (&cs)[8]) {
+    constexpr int HALF = D / 2;
+    const float2 *row = rope + (int64_t)pos * HALF;
+    if (STYLE == 0) {
+        const float4 *p = reinterpret_cast<const float4 *>(row + 8 * piece);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float4 v = p[w];
+            cs[2 * w] = make_float2(v.x, v.y);
+            cs[2 * w + 1] = make_float2(v.z, v.w);
+        }
+    } else {
+        const float4 *p = reinterpret_cast<const float4 *>(row + 4 * piece);
+        const float4 *q = reinterpret_cast<const float4 *>(row + HALF / 2 + 4 * piece);
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            const float4 v = p[w], u = q[w];
+            cs[2 * w] = make_float2(v.x, v.y);
+            cs[2 * w + 1] = make_float2(v.z, v.w);
+            cs[4 + 2 * w] = make_float2(u.x, u.y);
+            cs[4 + 2 * w + 1] = make_float2(u.z, u.w);
+        }
+    }
+}
+
+// one dword (2 elements) of each of the two 16-byte pieces a (dims d0..) and b (dims d0 + D/2..)
+template <int STYLE>
+__device__ inline void rotate_dword(uint32_t &pa, uint32_t &pb, const float2 (&cs)[8], int w) {
+    const float a0 = bf_lo(pa), a1 = bf_hi(pa);
+    const float b0 = bf_lo(pb), b1 = bf_hi(pb);
+    if (STYLE == 0) {
+        const float2 c0 = cs[2 * w], c1 = cs[2 * w + 1];
+        pa = pack_bf16(a0 * c0.x - b0 * c0.y, a1 * c1.x - b1 * c1.y);
+        pb = pack_bf16(b0 * c0.x + a0 * c0.y, b1 * c1.x + a1 * c1.y);
+    } else {
+        const float2 ca_ = cs[w], cb_ = cs[4 + w];
+        pa = pack_bf16(a0 * ca_.x - a1 * ca_.y, a1 * ca_.x + a0 * ca_.y);
+        pb = pack_bf16(b0 * cb_.x - b1 * cb_.y, b1 * cb_.x + b0 * cb_.y);
+    }
+}
+
+template <int D, int STYLE>
+__global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
+    constexpr int HALF = D / 2;
+    constexpr int KSTEPS = D / 16;           // k-steps of the S^T product
+    constexpr int DBLKS = D / 32;            // 32-row blocks of O^T
+    constexpr int PPR = D / 8;               // 16-byte pieces per row
+    constexpr int KPC = 64 / PPR;            // keys per 1 KiB chunk
+    constexpr int CHUNKS = BN / KPC;         // chunks per K (or V) tile
+    constexpr int CH = 1024 + KPC * 16;      // chunk stride in LDS (bytes)
+    constexpr int TILE = CHUNKS * CH;        // bytes of one K (or V) tile in LDS
+    constexpr int STAGE = 2 * TILE;
+    constexpr int NI = 2 * CHUNKS / NW;      // load instructions per thread and tile (K and V)
+    constexpr int ROT_TASKS = BN * PPR / 2;  // (key, piece pair) tasks of the rotary pass
+    static_assert(2 * CHUNKS % NW == 0, "chunks divide evenly over the wavefronts");
+    static_assert(NS * STAGE + kMaxPagesLds * 4 <= 160 * 1024, "LDS budget");
+
+    __shared__ __attribute__((aligned(16))) uint8_t ring[NS * STAGE];
+    __shared__ int32_t pg[kMaxPagesLds];
+
+    const WorkItem item = a.items[blockIdx.x];
+    if (item.seq < 0) return;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int lq = lane & 31;
+    const int half = lane >> 5;
+
+    const int c = item.seq;
+    const int g = item.kv_head;
+    const int G = a.n_q_heads / a.n_kv_heads;
+    const int n = a.n_keep[c];
+    const int q0 = a.cu_q[c];
+    const int32_t *table = a.block_table + (int64_t)c * a.max_pages;
+    const int Hkv = a.n_kv_heads;
+
+    const int row_last = item.row0 + item.n_rows - 1;          // last valid stacked row of the tile
+    const int kmax = n + row_last / G + 1;                      // keys this tile can see
+    const int n_tiles = (kmax + BN - 1) / BN;
+
+    // page ids of the visible context -> LDS
+    for (int i = tid; i < (kmax + kPageSize - 1) / kPageSize; i += NTHREADS) pg[i] = table[i];
+
+    // ---- this lane's query row --------------------------------------------------------------
+    const int r_raw = item.row0 + wave * 32 + lq;
+    const bool row_valid = r_raw <= row_last;
+    const int r = row_valid ? r_raw : row_last;
+    const int j = r / G;
+    const int head = g * G + (r - j * G);
+    const int qpos = n + j;                                      // keys 0..qpos are visible
+    const int wr_first = min(item.row0 + wave * 32, row_last);
+    const int wr_last = min(item.row0 + wave * 32 + 31, row_last);
+    const bool wave_live = item.row0 + wave * 32 <= row_last;
+    const int wq_min = n + wr_first / G;
+    const int wq_max = n + wr_last / G;
+
+    bf16x8 Qf[KSTEPS];
+    {
+        const uint16_t *qrow = a.q + ((int64_t)(q0 + j) * a.n_q_heads + head) * D;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS / 2; ++ks) {
+            const int piece = 2 * ks + half;
+            uint4 x = *reinterpret_cast<const uint4 *>(qrow + 8 * piece);
+            uint4 y = *reinterpret_cast<const uint4 *>(qrow + HALF + 8 * piece);
+            float2 cs[8];
+            load_cs<D, STYLE>(a.rope, qpos, piece, cs);
+            uint32_t *px = reinterpret_cast<uint32_t *>(&x), *py = reinterpret_cast<uint32_t *>(&y);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) rotate_dword<STYLE>(px[w], py[w], cs, w);
+            Qf[ks] = __builtin_bit_cast(bf16x8, x);
+            Qf[ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, y);
+        }
+    }
+
+    // ---- rotary pass: this thread's (key, piece pair) of every K tile ------------------------------
+    const bool rot_active = ROT_TASKS >= NTHREADS || tid < ROT_TASKS;
+    const int rot_kk = tid / (PPR / 2);
+    const int rot_pr = tid % (PPR / 2);
+    const int rot_off = (rot_kk / KPC) * CH + (rot_pr * KPC + rot_kk % KPC) * 16;   // piece rot_pr; partner +512
+    constexpr int ROT_PARTNER = (PPR / 2) * KPC * 16;
+    float2 k_step[8], k_cs[8];
+    load_cs<D, STYLE>(a.rope, BN, rot_pr, k_step);
+    load_cs<D, STYLE>(a.rope, rot_active ? rot_kk : 0, rot_pr, k_cs);
+    uint4 kx, ky;
+
+    // ---- operand addresses inside a stage ---------------------------------------------------------------
+    // K, A operand of S^T: key 32mb + lq, piece 2ks + half  ->  + ks * 2*KPC*16 as an immediate
+    int k_rd[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+        const int key = 32 * mb + lq;
+        k_rd[mb] = (key / KPC) * CH + (half * KPC + key % KPC) * 16;
+    }
+    // V, A operand of O^T via transposing reads: lane s of a 16-lane group points at key k0 + s/4,
+    // dims d0 + 4*(s%4) .. +3 and receives dims d0 + s of keys k0..k0+3
+    const int s16 = lane & 15;
+    const int dsel = (lane >> 4) & 1;
+    int v_rd;
+    {
+        const int piece_lo = 2 * dsel + ((s16 & 3) >> 1);      // + 4*db
+        const int kl = (D == 128) ? (s16 >> 2) : (4 * half + (s16 >> 2));
+        v_rd = TILE + (piece_lo * KPC + kl) * 16 + (s16 & 1) * 8 + ((D == 128) ? half * CH : 0);
+    }
+
+    // ---- loads: chunk `wave + 8*i` of the 2*CHUNKS chunks [K | V] of a tile -----------------------------
+    int ld_tok[NI], ld_goff[NI], ld_loff[NI];
+    bool ld_is_v[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int cid = wave + NW * i;
+        ld_is_v[i] = cid >= CHUNKS;
+        const int jch = cid % CHUNKS;
+        const int piece = lane / KPC, kl = lane % KPC;
+        ld_tok[i] = jch * KPC + kl;                 // key inside the tile
+        ld_goff[i] = piece * 8;                     // element offset inside the row
+        ld_loff[i] = (ld_is_v[i] ? TILE : 0) + jch * CH;
+    }
+    auto issue = [&](int tile) {
+        const int kt0 = tile * BN;
+        uint8_t *stage = ring + (tile % NS) * STAGE;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int t = min(kt0 + ld_tok[i], kmax - 1);
+            const int page = pg[t >> 4];
+            const uint16_t *base = ld_is_v[i] ? a.v_pool : a.k_pool;
+            const uint16_t *src = base + (((int64_t)page * Hkv + g) * kPageSize + (t & 15)) * D + ld_goff[i];
+            dma16(src, __builtin_amdgcn_readfirstlane(lds_offset(stage + ld_loff[i])));
+        }
+    };
+
+    auto rot_read = [&](uint8_t *kst) {
+        if (rot_active) {
+            kx = *reinterpret_cast<const uint4 *>(kst + rot_off);
+            ky = *reinterpret_cast<const uint4 *>(kst + rot_off + ROT_PARTNER);
+        }
+    };
+    auto rot_part = [&](uint8_t *kst, int w) {
+        if (rot_active) {
+            uint32_t *pa = reinterpret_cast<uint32_t *>(&kx), *pb = reinterpret_cast<uint32_t *>(&ky);
+            rotate_dword<STYLE>(pa[w], pb[w], k_cs, w);
+#pragma unroll
+            for (int e2 = 0; e2 < 2; ++e2) {
+                const int e = (STYLE == 0) ? 2 * w + e2 : w + 4 * e2;
+                const float2 o = k_cs[e], st = k_step[e];
+                k_cs[e] = make_float2(o.x * st.x - o.y * st.y, o.y * st.x + o.x * st.y);
+            }
+            if (w == 3) {
+                *reinterpret_cast<uint4 *>(kst + rot_off) = kx;
+                *reinterpret_cast<uint4 *>(kst + rot_off + ROT_PARTNER) = ky;
+            }
+        }
+    };
+
+    f32x16 O[DBLKS];
+#pragma unroll
+    for (int db = 0; db < DBLKS; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[db][i] = 0.f;
+    float m_run = -INFINITY;
+    float l_run = 0.f;
+    const float cscale = a.softmax_scale * 1.4426950408889634f;
+
+    // ---- prologue ---------------------------------------------------------------------------------------
+    __syncthreads();                     // page ids are in LDS
+    issue(0);
+    if (n_tiles > 1) issue(1);
+    if (n_tiles > 2) issue(2);
+    if (n_tiles > 2) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }   // tiles 0 and 1 have landed
+    __syncthreads();
+    rot_read(ring);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) rot_part(ring, w);
+    __syncthreads();
+
+    auto walk = [&](int tile, auto interior_tag, auto live_tag) {
+        constexpr bool INTERIOR = decltype(interior_tag)::value;
+        constexpr bool LIVE = decltype(live_tag)::value;
+        const int kt0 = tile * BN;
+        uint8_t *st = ring + (tile % NS) * STAGE;
+        uint8_t *st_next = ring + ((tile + 1) % NS) * STAGE;
+        const bool compute = LIVE && (INTERIOR || kt0 <= wq_max);
+        const bool has_next = INTERIOR || tile + 1 < n_tiles;
+
+        // the stage multiplied in the previous iteration is free: refill it three tiles ahead
+        if (INTERIOR || tile + NS - 1 < n_tiles) issue(tile + NS - 1);
+        if (has_next) rot_read(st_next);
+
+        f32x16 S[2];
+        if (compute) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) S[mb][i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + k_rd[mb] + ks * (2 * KPC * 16));
+                    S[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[ks], S[mb], 0, 0, 0);
+                }
+                if (has_next && ks % (KSTEPS / 4) == KSTEPS / 4 - 1) rot_part(st_next, ks / (KSTEPS / 4));
+            }
+        } else if (has_next) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) rot_part(st_next, w);
+        }
+
+        if (compute) {
+            if (!INTERIOR && kt0 + BN - 1 > wq_min) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = kt0 + 32 * mb + (i >> 2) * 8 + half * 4 + (i & 3);
+                        if (key > qpos) S[mb][i] = -INFINITY;
+                    }
+            }
+            float mx = S[0][0];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[mb][i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const bool raise = (mx - m_run) * cscale > 8.0f;
+            if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+                const float m_new = raise ? mx : m_run;
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * cscale);
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DBLKS; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) O[db][i] *= alpha;
+            }
+            const float mc = m_run * cscale;
+            float psum = 0.f;
+#pragma unroll
+            for (int ks2 = 0; ks2 < 4; ++ks2) {
+                const int mb = ks2 >> 1, kk2 = ks2 & 1;
+                uint32_t pk[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][8 * kk2 + 2 * w], cscale, -mc));
+                    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][8 * kk2 + 2 * w + 1], cscale, -mc));
+                    psum += p0 + p1;
+                    pk[w] = pack_bf16(p0, p1);
+                }
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+#pragma unroll
+                for (int db = 0; db < DBLKS; ++db) {
+                    // keys 16ks2 + 4half + 0..3 and 16ks2 + 8 + 4half + 0..3 of dims 32db + lq
+                    constexpr int KEY_STEP = (D == 128) ? 1 : 0;   // D = 128: 4 keys per chunk, a quad is a chunk
+                    const int o0 = (D == 128 ? (4 * ks2) * CH : (2 * ks2) * CH) + 4 * db * KPC * 16;
+                    const int o1 = (D == 128 ? (4 * ks2 + 2) * CH : (2 * ks2 + 1) * CH) + 4 * db * KPC * 16;
+                    (void)KEY_STEP;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(st + v_rd + o0));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(st + v_rd + o1));
+                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb, O[db], 0, 0, 0);
+                }
+            }
+            l_run += psum;
+        }
+
+        // tile+2 must have landed before anyone rotates it in the next iteration; the loads of tile+3
+        // (issued at the top of this iteration) may stay in flight
+        if (INTERIOR) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }
+        __syncthreads();
+    };
+
+    const int first_qpos = n + item.row0 / G;
+    const int n_interior = max(0, min((first_qpos + 1) / BN, kmax / BN - NS));
+    int tile = 0;
+    if (wave_live) {
+        for (; tile < n_interior; ++tile) walk(tile, std::true_type{}, std::true_type{});
+        for (; tile < n_tiles; ++tile) walk(tile, std::false_type{}, std::true_type{});
+    } else {
+        for (; tile < n_interior; ++tile) walk(tile, std::true_type{}, std::false_type{});
+        for (; tile < n_tiles; ++tile) walk(tile, std::false_type{}, std::false_type{});
+    }
+
+    // ---- epilogue: normalise and store --------------------------------------------------------------
+    const float l_all = l_run + __shfl_xor(l_run, 32);
+    if (row_valid) {
+        const float inv = 1.f / l_all;
+        uint16_t *orow = a.out + ((int64_t)(q0 + j) * a.n_q_heads + head) * D;
+#pragma unroll
+        for (int db = 0; db < DBLKS; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int d = 32 * db + i4 * 8 + half * 4;
+                uint2 o;
+                o.x = pack_bf16(O[db][4 * i4] * inv, O[db][4 * i4 + 1] * inv);
+                o.y = pack_bf16(O[db][4 * i4 + 2] * inv, O[db][4 * i4 + 3] * inv);
+                *reinterpret_cast<uint2 *>(orow + d) = o;
+            }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attn_dma(const AttnArgs &a, hipStream_t stream) {
+    if (a.n_items <= 0) return hipSuccess;
+    if (a.tile_rows != 256) return hipErrorInvalidValue;
+    dim3 grid(a.n_items), block(NTHREADS);
+    if (a.head_dim == 128 && a.rope_style == 0)
+        hipLaunchKernelGGL((attn_dma_kernel<128, 0>), grid, block, 0, stream, a);
+    else if (a.head_dim == 128)
+        hipLaunchKernelGGL((attn_dma_kernel<128, 1>), grid, block, 0, stream, a);
+    else if (a.head_dim == 64 && a.rope_style == 0)
+        hipLaunchKernelGGL((attn_dma_kernel<64, 0>), grid, block, 0, stream, a);
+    else if (a.head_dim == 64)
+        hipLaunchKernelGGL((attn_dma_kernel<64, 1>), grid, block, 0, stream, a);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace ca

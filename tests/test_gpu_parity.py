@@ -131,7 +131,7 @@ def test_save_arbitrary_ranges_bit_exact(case):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [1, 0], ids=["scalar", "mfma"])
+@pytest.mark.parametrize("variant", [1, 0, 2], ids=["scalar", "mfma", "dma"])
 def test_attention_matches_oracle(case, variant):
     run = GpuRun(case, tier="device", attn_variant=variant)
     try:
@@ -150,7 +150,7 @@ def test_attention_matches_oracle(case, variant):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [1, 0], ids=["scalar", "mfma"])
+@pytest.mark.parametrize("variant", [1, 0, 2], ids=["scalar", "mfma", "dma"])
 def test_attention_peaky_softmax(variant):
     """Queries scaled x6: a handful of keys dominate each row and outputs are O(1), so a wrong key,
     a wrong mask edge or a wrong position cannot hide under the tolerance.  Scores grow with the
@@ -171,7 +171,7 @@ def test_attention_peaky_softmax(variant):
             K = np.concatenate([w(case.tensor(0, "k_hist", c))[s:], w(case.tensor(0, "k_new", c))])
             V = np.concatenate([w(case.tensor(0, "v_hist", c))[s:], w(case.tensor(0, "v_new", c))])
             Q = w(case.tensor(0, "q", c))
-            if variant == 0:
+            if variant != 1:
                 Kr = np.array([[oracle.rope(K[t, g], t) for g in range(K.shape[1])] for t in range(K.shape[0])])
                 Qr = np.array([[oracle.rope(Q[j, h], n + j) for h in range(Q.shape[1])] for j in range(ln)])
                 Kr = w(f32_to_bf16_bits(Kr.astype(np.float32)))

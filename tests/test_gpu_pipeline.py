@@ -133,8 +133,9 @@ def test_multi_turn_reuse_with_truncation_equals_recompute():
             saved = saved + new
 
 
+@pytest.mark.parametrize("variant", [0, 2], ids=["mfma", "dma"])
 @pytest.mark.parametrize("index", [2, 3, 4, 5])
-def test_full_size_layer_sampled_against_oracle(index):
+def test_full_size_layer_sampled_against_oracle(index, variant):
     """One layer at the benchmark's full shapes and length mix, in the launch configuration the
     benchmark times (HBM-resident tier, automatic tile size); outputs of sampled (conversation, head)
     pairs are checked element by element, the data movement is checked on whole sampled conversations."""
@@ -148,7 +149,7 @@ def test_full_size_layer_sampled_against_oracle(index):
         keep = np.zeros(cfg["batch"], np.int32)
     case = Case(wl.hist_len, wl.new_len, keep, cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], seed=index,
                 window=cfg["window"])
-    run = GpuRun(case, tier="device")
+    run = GpuRun(case, tier="device", attn_variant=variant)
     try:
         run.rebase()
         run.run_layer(0)
