@@ -78,7 +78,9 @@ typedef struct {
     int32_t load_mode;       /* 0: choose per source pointer; 1: copy into a staging slot,    */
                              /* then unpack; 2: the unpack kernel reads the source in place   */
                              /* (source must be device-accessible)                            */
-    int32_t attn_variant;    /* 0: MFMA kernel; 1: scalar fp32 kernel (slow, for checking)    */
+    int32_t attn_variant;    /* 0: MFMA kernel, K/V staged through registers; 1: scalar fp32   */
+                             /* kernel (slow, for checking); 2: MFMA kernel, K/V loaded        */
+                             /* straight into LDS (256-row tiles, max_positions <= 32768)      */
     int32_t attn_tile_rows;  /* stacked query rows per workgroup of the MFMA kernel: 128, 256,  */
                              /* or 0 = choose per batch                                        */
     int32_t require_load;    /* 1: attention on a layer with kept history that was not loaded */

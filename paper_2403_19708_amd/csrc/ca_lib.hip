@@ -953,6 +953,7 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
         CA_HIP(ctx, launch_attn_ref(a, stream));
     } else if (c.attn_variant == 2) {
         CA_HIP(ctx, launch_attn_dma(a, stream));
+
     } else {
         CA_HIP(ctx, launch_attn_mfma(a, stream));
     }
