@@ -49,6 +49,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
     ap.add_argument("--load-mode", type=int, default=0, help="library load_mode for the pinned-host leg (0 staged copies, 2 kernels access the host tier in place)")
+    ap.add_argument("--save-mode", type=int, default=0, help="library save_mode for the pinned-host leg")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging only; marks the result invalid)")
     return ap.parse_args()
 
@@ -145,7 +146,7 @@ def main():
         base, esz = bufs[layer].data_ptr(), row * 2
         return [base + int(tier_off[c]) * esz for c in range(B)]
 
-    conf = ca.Config(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=W, load_mode=args.load_mode,
+    conf = ca.Config(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=W, load_mode=args.load_mode, save_mode=args.save_mode,
                      pipeline_depth=2, max_seqs=B, max_batch_kv_tokens=tot_k + 64, max_batch_q_tokens=tot_q + 16)
     ctx = ca.Context(conf)
     stream = torch.cuda.current_stream()
@@ -212,6 +213,56 @@ def main():
                     frac=kern[dominant]["gbs"] / HBM_PEAK_GBS, traffic=None)
     roof["avg_launch_us"] = kern[dominant]["us"]
     roof["algorithmic_bytes_per_launch"] = kern[dominant]["bytes"]
+
+    # ---- each kernel alone (no other stream active): what the kernels do without contention -----------------
+    iso = {}
+    n_iso = min(L, 4)
+    ctx.profile_enable(True)
+    for l in range(n_iso):
+        ctx.sync(); torch.cuda.synchronize()
+        ctx.rope_rebase(hist, keep_start, new, block_table, num_pages, stream)
+        ctx.sync(); torch.cuda.synchronize()
+        ctx.kv_load_layer(l, dev_k[l], dev_v[l], k_pool[l], v_pool[l])
+        ctx.sync(); torch.cuda.synchronize()
+        ctx.kv_append_layer(l, k_new[l], v_new[l], k_pool[l], v_pool[l], stream)
+        ctx.sync(); torch.cuda.synchronize()
+        ctx.cached_prefill_attn(l, q[l], k_pool[l], v_pool[l], out[l], scale, stream)
+        ctx.sync(); torch.cuda.synchronize()
+        ctx.kv_save_layer(l, k_pool[l], v_pool[l], dev_k[l], dev_v[l], after_stream=stream)
+        ctx.sync(); torch.cuda.synchronize()
+    ctx.profile_enable(False)
+    for kname, nbytes in (("attn", attn_bytes), ("unpack", unpack_bytes), ("append", append_bytes), ("pack", pack_bytes)):
+        ms, cnt = ctx.profile_read(kname)
+        us = ms / cnt * 1e3 if cnt else None
+        iso[kname] = {"avg_launch_us": us, "gbs": nbytes / (us * 1e-6) / 1e9 if us else None,
+                      "frac_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS if us else None}
+    iso["attn"]["tflops"] = flops_layer / (iso["attn"]["avg_launch_us"] * 1e-6) / 1e12
+    iso["attn"]["frac_mfma_peak"] = iso["attn"]["tflops"] / MFMA_BF16_PEAK_TFLOPS
+    iso["attn"]["frac_binding_roofline"] = max(t_mfma_us, t_hbm_us) / iso["attn"]["avg_launch_us"]
+    log("[bench] isolated: " + ", ".join(f"{k} {v['avg_launch_us']:.1f} us" for k, v in iso.items()))
+
+    # ---- a plain device copy of known size: the reference the HBM byte counters are scaled by ---------------
+    cal_n = 256 * 1024 * 1024 // 2
+    cal_src = torch.empty(cal_n, dtype=torch.bfloat16, device=dev).normal_()
+    cal_dst = torch.empty_like(cal_src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    cal_dst.copy_(cal_src)
+    e0.record(); cal_dst.copy_(cal_src); e1.record(); torch.cuda.synchronize()
+    copy_gbs = 2 * cal_n * 2 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del cal_src, cal_dst
+
+    # HBM traffic per launch of the dominant kernel, from rocprofv3 counter runs (kept under profiles/)
+    traffic_file = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{args.config}.txt")
+    if os.path.exists(traffic_file):
+        kv = {}
+        for line in open(traffic_file):
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                kv[k.strip()] = v.split("#")[0].strip()
+        key = {"attn": "attn", "unpack": "unpack", "append": "append", "pack": "pack"}[dominant] + "_bytes_per_launch"
+        if key in kv:
+            roof["traffic"] = float(kv[key])
 
     # ---- sampled parity check of layer 0 against the oracle ---------------------------------------------
     parity = None
@@ -319,6 +370,8 @@ def main():
                  "avg_launch_us": kern["attn"]["us"], "gbs": kern["attn"]["gbs"], "frac_hbm_peak": kern["attn"]["gbs"] / HBM_PEAK_GBS,
                  "binding_roofline": attn_bound, "roofline_floor_us": max(t_mfma_us, t_hbm_us),
                  "frac_binding_roofline": max(t_mfma_us, t_hbm_us) / kern["attn"]["us"]},
+        "isolated": iso,
+        "device_copy_gbs": copy_gbs,
         "kv_move": {k: {"avg_launch_us": kern[k]["us"], "gbs": kern[k]["gbs"],
                         "frac_hbm_peak": (kern[k]["gbs"] / HBM_PEAK_GBS) if kern[k]["gbs"] else None}
                     for k in ("unpack", "append", "pack")},

@@ -78,6 +78,9 @@ typedef struct {
     int32_t load_mode;       /* 0: choose per source pointer; 1: copy into a staging slot,    */
                              /* then unpack; 2: the unpack kernel reads the source in place   */
                              /* (source must be device-accessible)                            */
+    int32_t save_mode;       /* like load_mode, for ca_kv_save_layer: 0 choose per destination  */
+                             /* (pinned host: staging slot + copy-out), 1 always stage, 2 the   */
+                             /* pack kernel writes the destination in place                     */
     int32_t attn_variant;    /* 0: MFMA kernel, K/V staged through registers; 1: scalar fp32   */
                              /* kernel (slow, for checking); 2: MFMA kernel, K/V loaded        */
                              /* straight into LDS (256-row tiles, max_positions <= 32768)      */

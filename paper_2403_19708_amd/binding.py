@@ -38,7 +38,7 @@ class _CConfig(C.Structure):
                 ("head_dim", C.c_int32), ("page_size", C.c_int32), ("max_positions", C.c_int32),
                 ("rope_base", C.c_float), ("rope_style", C.c_int32), ("pipeline_depth", C.c_int32),
                 ("max_seqs", C.c_int32), ("max_batch_kv_tokens", C.c_int64),
-                ("max_batch_q_tokens", C.c_int64), ("load_mode", C.c_int32),
+                ("max_batch_q_tokens", C.c_int64), ("load_mode", C.c_int32), ("save_mode", C.c_int32),
                 ("attn_variant", C.c_int32), ("attn_tile_rows", C.c_int32), ("require_load", C.c_int32),
                 ("device", C.c_int32)]
 
@@ -119,6 +119,7 @@ class Config:
     max_batch_kv_tokens: int = 1 << 16
     max_batch_q_tokens: int = 1 << 14
     load_mode: int = 0
+    save_mode: int = 0
     attn_variant: int = 0
     attn_tile_rows: int = 0
     require_load: int = 1

@@ -179,6 +179,7 @@ void ca_config_default(ca_config *c) {
     c->max_batch_kv_tokens = 1 << 16;
     c->max_batch_q_tokens = 1 << 14;
     c->load_mode = 0;
+    c->save_mode = 0;
     c->attn_variant = 0;
     c->attn_tile_rows = 0;
     c->require_load = 1;
@@ -227,6 +228,10 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
         c->max_batch_q_tokens < 1 || c->max_batch_q_tokens > c->max_batch_kv_tokens) {
         set_err(err, err_len, "max_batch_kv_tokens / max_batch_q_tokens out of range");
         return CA_ERR_OUT_OF_RANGE;
+    }
+    if (c->save_mode < 0 || c->save_mode > 2) {
+        set_err(err, err_len, "save_mode (0..2) out of range");
+        return CA_ERR_INVALID_ARG;
     }
     if (c->load_mode < 0 || c->load_mode > 2 || c->attn_variant < 0 || c->attn_variant > 2) {
         set_err(err, err_len, "load_mode (0..2) or attn_variant (0..2) out of range");
@@ -850,7 +855,7 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
         total += r[i].e - r[i].b;
     }
     if (total > c.max_batch_kv_tokens) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_kv_save_layer: %lld tokens exceed a staging slot", (long long)total);
-    const bool staged = c.load_mode == 1 || (c.load_mode == 0 && any_host);
+    const bool staged = c.save_mode == 1 || (c.save_mode == 0 && any_host);
 
     // saving starts after the producer of this layer's K/V
     CA_HIP(ctx, hipEventRecord(ctx->ev_after, (hipStream_t)after_stream));

@@ -86,7 +86,7 @@ def test_rebase_metadata_bit_exact(case):
 
 @pytest.mark.parametrize("tier,mode", [("pinned", 0), ("pinned", 2), ("device", 0), ("device", 1)])
 def test_load_append_save_bit_exact(case, tier, mode):
-    run = GpuRun(case, tier=tier, load_mode=mode)
+    run = GpuRun(case, tier=tier, load_mode=mode, save_mode=mode)
     try:
         run.rebase()
         run.load(0)
