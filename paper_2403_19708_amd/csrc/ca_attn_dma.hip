@@ -40,9 +40,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-constexpr int BN = 64;    // keys per tile
-constexpr int NW = 8;     // wavefronts per workgroup
-constexpr int NTHREADS = 64 * NW;
 constexpr int NS = 4;     // LDS stages
 constexpr int kMaxPagesLds = 2048;   // page ids kept in LDS: contexts up to 32768 tokens
 
@@ -60,6 +57,13 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
 // makes exact.  lds_base must be wave-uniform.
 __device__ inline void dma16(const void *src, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(src) : "memory", "m0");
+}
+
+// same, with the address split into a wave-uniform 64-bit base (scalar registers) and a 32-bit
+// per-lane byte offset: no vector arithmetic per load
+__device__ inline void dma16_sbase(const void *base_uniform, uint32_t lane_off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 : : "s"(lds_base), "v"(lane_off), "s"(base_uniform) : "memory", "m0");
 }
 
 __device__ inline uint32_t lds_offset(const void *p) {
@@ -112,8 +116,15 @@ __device__ inline void rotate_dword(uint32_t &pa, uint32_t &pb, const float2 (&c
     }
 }
 
-template <int D, int STYLE>
-__global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
+// NW wavefronts (32 stacked query rows each) per workgroup, key tiles of BN.  Two shapes are built:
+// NW = 8, BN = 64 (one workgroup per compute unit, 256-row tiles) and NW = 4, BN = 32 (two independent
+// workgroups per compute unit, 128-row tiles: the two wavefronts that share a SIMD then belong to
+// different workgroups, are not in lock step, and one's matrix products run under the other's softmax).
+template <int D, int STYLE, int NW, int BN>
+__global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
+    constexpr int NTHREADS = 64 * NW;
+    constexpr int MB = BN / 32;              // 32-key blocks of S^T per tile
+    constexpr int KS2 = BN / 16;             // 16-key steps of the second product per tile
     constexpr int HALF = D / 2;
     constexpr int KSTEPS = D / 16;           // k-steps of the S^T product
     constexpr int DBLKS = D / 32;            // 32-row blocks of O^T
@@ -126,7 +137,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
     constexpr int NI = 2 * CHUNKS / NW;      // load instructions per thread and tile (K and V)
     constexpr int ROT_TASKS = BN * PPR / 2;  // (key, piece pair) tasks of the rotary pass
     static_assert(2 * CHUNKS % NW == 0, "chunks divide evenly over the wavefronts");
-    static_assert(NS * STAGE + kMaxPagesLds * 4 <= 160 * 1024, "LDS budget");
+    static_assert((NW == 8 ? 1 : 2) * (NS * STAGE + kMaxPagesLds * 4) <= 160 * 1024, "LDS budget");
 
     __shared__ __attribute__((aligned(16))) uint8_t ring[NS * STAGE];
     __shared__ int32_t pg[kMaxPagesLds];
@@ -199,9 +210,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
 
     // ---- operand addresses inside a stage ---------------------------------------------------------------
     // K, A operand of S^T: key 32mb + lq, piece 2ks + half  ->  + ks * 2*KPC*16 as an immediate
-    int k_rd[2];
+    int k_rd[MB];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
+    for (int mb = 0; mb < MB; ++mb) {
         const int key = 32 * mb + lq;
         k_rd[mb] = (key / KPC) * CH + (half * KPC + key % KPC) * 16;
     }
@@ -242,6 +253,25 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
         }
     };
 
+    // Interior tiles need no clamping: all lanes of one load read rows of the same page, so the page
+    // lookup and the whole address up to the lane's constant offset are wave-uniform (scalar ALU).
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t ld_lane_off = (uint32_t)((lane % KPC) * D + (lane / KPC) * 8) * 2u;
+    auto issue_interior = [&](int tile) {
+        const int kt0 = tile * BN;
+        const uint32_t stage = __builtin_amdgcn_readfirstlane(lds_offset(ring)) + (uint32_t)((tile % NS) * STAGE);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int cid = wave_u + NW * i;
+            const bool is_v = cid >= CHUNKS;
+            const int jch = cid % CHUNKS;
+            const int t0 = kt0 + jch * KPC;                                 // first key of the chunk
+            const int page = __builtin_amdgcn_readfirstlane(pg[t0 >> 4]);
+            const uint16_t *base = (is_v ? a.v_pool : a.k_pool) + (((int64_t)page * Hkv + g) * kPageSize + (t0 & 15)) * D;
+            dma16_sbase(base, ld_lane_off, stage + (uint32_t)((is_v ? TILE : 0) + jch * CH));
+        }
+    };
+
     auto rot_read = [&](uint8_t *kst) {
         if (rot_active) {
             kx = *reinterpret_cast<const uint4 *>(kst + rot_off);
@@ -273,6 +303,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
     float m_run = -INFINITY;
     float l_run = 0.f;
     const float cscale = a.softmax_scale * 1.4426950408889634f;
+    const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
     // ---- prologue ---------------------------------------------------------------------------------------
     __syncthreads();                     // page ids are in LDS
@@ -296,19 +327,20 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
         const bool has_next = INTERIOR || tile + 1 < n_tiles;
 
         // the stage multiplied in the previous iteration is free: refill it three tiles ahead
-        if (INTERIOR || tile + NS - 1 < n_tiles) issue(tile + NS - 1);
+        if (INTERIOR) issue_interior(tile + NS - 1);
+        else if (tile + NS - 1 < n_tiles) issue(tile + NS - 1);
         if (has_next) rot_read(st_next);
 
-        f32x16 S[2];
+        f32x16 S[MB];
         if (compute) {
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) S[mb][i] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb) {
+                for (int mb = 0; mb < MB; ++mb) {
                     const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + k_rd[mb] + ks * (2 * KPC * 16));
                     S[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[ks], S[mb], 0, 0, 0);
                 }
@@ -322,7 +354,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
         if (compute) {
             if (!INTERIOR && kt0 + BN - 1 > wq_min) {
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+                for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = kt0 + 32 * mb + (i >> 2) * 8 + half * 4 + (i & 3);
@@ -331,7 +363,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
             }
             float mx = S[0][0];
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[mb][i]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -349,15 +381,16 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
             const float mc = m_run * cscale;
             float psum = 0.f;
 #pragma unroll
-            for (int ks2 = 0; ks2 < 4; ++ks2) {
+            for (int ks2 = 0; ks2 < KS2; ++ks2) {
                 const int mb = ks2 >> 1, kk2 = ks2 & 1;
                 uint32_t pk[4];
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][8 * kk2 + 2 * w], cscale, -mc));
                     const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][8 * kk2 + 2 * w + 1], cscale, -mc));
-                    psum += p0 + p1;
                     pk[w] = pack_bf16(p0, p1);
+                    // the denominator sums the rounded probabilities, the very values the second product uses
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[w]), ones2, psum, false);
                 }
                 const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
 #pragma unroll
@@ -411,23 +444,29 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_dma_kernel(AttnArgs a) {
     }
 }
 
+template <int NW, int BN>
+hipError_t launch_shape(const AttnArgs &a, hipStream_t stream) {
+    dim3 grid(a.n_items), block(64 * NW);
+    if (a.head_dim == 128 && a.rope_style == 0)
+        hipLaunchKernelGGL((attn_dma_kernel<128, 0, NW, BN>), grid, block, 0, stream, a);
+    else if (a.head_dim == 128)
+        hipLaunchKernelGGL((attn_dma_kernel<128, 1, NW, BN>), grid, block, 0, stream, a);
+    else if (a.head_dim == 64 && a.rope_style == 0)
+        hipLaunchKernelGGL((attn_dma_kernel<64, 0, NW, BN>), grid, block, 0, stream, a);
+    else if (a.head_dim == 64)
+        hipLaunchKernelGGL((attn_dma_kernel<64, 1, NW, BN>), grid, block, 0, stream, a);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_attn_dma(const AttnArgs &a, hipStream_t stream) {
     if (a.n_items <= 0) return hipSuccess;
-    if (a.tile_rows != 256) return hipErrorInvalidValue;
-    dim3 grid(a.n_items), block(NTHREADS);
-    if (a.head_dim == 128 && a.rope_style == 0)
-        hipLaunchKernelGGL((attn_dma_kernel<128, 0>), grid, block, 0, stream, a);
-    else if (a.head_dim == 128)
-        hipLaunchKernelGGL((attn_dma_kernel<128, 1>), grid, block, 0, stream, a);
-    else if (a.head_dim == 64 && a.rope_style == 0)
-        hipLaunchKernelGGL((attn_dma_kernel<64, 0>), grid, block, 0, stream, a);
-    else if (a.head_dim == 64)
-        hipLaunchKernelGGL((attn_dma_kernel<64, 1>), grid, block, 0, stream, a);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (a.tile_rows == 256) return launch_shape<8, 64>(a, stream);
+    if (a.tile_rows == 128) return launch_shape<4, 32>(a, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace ca

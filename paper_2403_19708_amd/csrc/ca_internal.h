@@ -91,7 +91,7 @@ constexpr int kRopeMinRows = 256;       // the kernels read table rows below thi
 
 hipError_t launch_attn_mfma(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_ref(const AttnArgs &args, hipStream_t stream);
-hipError_t launch_attn_dma(const AttnArgs &args, hipStream_t stream);   // tile_rows must be 256
+hipError_t launch_attn_dma(const AttnArgs &args, hipStream_t stream);
 constexpr int kAttnDmaMaxPositions = 32768;   // page ids of one conversation are kept in LDS
 
 }  // namespace ca

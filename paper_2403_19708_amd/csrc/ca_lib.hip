@@ -237,8 +237,8 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
         set_err(err, err_len, "load_mode (0..2) or attn_variant (0..2) out of range");
         return CA_ERR_INVALID_ARG;
     }
-    if (c->attn_variant == 2 && (c->max_positions > kAttnDmaMaxPositions || c->attn_tile_rows == 128)) {
-        set_err(err, err_len, "attn_variant 2 needs max_positions <= %d and 256-row tiles", kAttnDmaMaxPositions);
+    if (c->attn_variant == 2 && c->max_positions > kAttnDmaMaxPositions) {
+        set_err(err, err_len, "attn_variant 2 needs max_positions <= %d", kAttnDmaMaxPositions);
         return CA_ERR_UNSUPPORTED;
     }
     if (c->attn_tile_rows != 0 && c->attn_tile_rows != 128 && c->attn_tile_rows != 256) {
@@ -548,7 +548,7 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
         const int G = c.n_q_heads / c.n_kv_heads;
         // 256-row tiles (8 wavefronts) halve the K/V re-reads and the rotary work per row when a
         // (conversation, kv head) has more than 128 stacked rows; small turns keep 128-row tiles
-        int tile = c.attn_variant == 2 ? 256 : c.attn_tile_rows;
+        int tile = c.attn_tile_rows;
         if (tile == 0) {
             int most = 0;
             for (int i = 0; i < B; ++i) most = std::max(most, b->new_len[i] * G);

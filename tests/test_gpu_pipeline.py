@@ -17,10 +17,10 @@ def check_contract(got, want, where):
     assert err.max() <= 2e-2 and err.mean() <= 2e-3, (where, f"max-abs {err.max():.3e} mean-abs {err.mean():.3e}")
 
 
-def run_stack(case, tier, depth, mode, sync_every_op=False, tile=0):
+def run_stack(case, tier, depth, mode, sync_every_op=False, tile=0, variant=0):
     """Runs every layer the way the benchmark does: all loads queued first, then per layer
     append -> attention -> save.  Returns the outputs and the saved tier as bits."""
-    run = GpuRun(case, tier=tier, pipeline_depth=depth, load_mode=mode, attn_tile_rows=tile)
+    run = GpuRun(case, tier=tier, pipeline_depth=depth, load_mode=mode, attn_tile_rows=tile, attn_variant=variant)
     try:
         stream = torch.cuda.Stream()
         with torch.cuda.stream(stream):
@@ -65,10 +65,11 @@ def test_pipeline_orderings_give_identical_bits():
             at += int(case.new_len[c])
 
 
-def test_both_tile_sizes_agree_with_oracle():
+@pytest.mark.parametrize("variant", [0, 2], ids=["mfma", "dma"])
+def test_both_tile_sizes_agree_with_oracle(variant):
     case = Case([500, 90], [200, 31], [37, 0], 8, 2, 128, seed=52)
     for tile in (128, 256):
-        out, _ = run_stack(case, "device", 2, 0, tile=tile)
+        out, _ = run_stack(case, "device", 2, 0, tile=tile, variant=variant)
         at = 0
         for c in range(case.B):
             check_contract(bf16_bits_to_f64(out[0][at:at + int(case.new_len[c])]), case.oracle_out(0, c), (tile, c))
