@@ -203,11 +203,13 @@ def main():
     attn_bound = "mfma" if t_mfma_us > t_hbm_us else "hbm"
     # the dominant kernel is the one with the largest share of a step's GPU time
     dominant = max(kern, key=lambda k: kern[k]["us"] or 0.0)
+    # the library's default choice of attention kernel: LDS-direct loads while the window fits its page table
+    attn_kernel = "attn_dma_kernel" if W <= 32768 else "attn_mfma_kernel"
     if dominant == "attn" and attn_bound == "mfma":
-        roof = dict(kernel="attn_mfma_kernel", bound="mfma", achieved=attn_tflops, peak=MFMA_BF16_PEAK_TFLOPS,
+        roof = dict(kernel=attn_kernel, bound="mfma", achieved=attn_tflops, peak=MFMA_BF16_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=attn_tflops / MFMA_BF16_PEAK_TFLOPS, traffic=None)
     else:
-        name = {"attn": "attn_mfma_kernel", "unpack": "move_kernel<to_pool> (load)", "append": "move_kernel<to_pool> (append)",
+        name = {"attn": attn_kernel, "unpack": "move_kernel<to_pool> (load)", "append": "move_kernel<to_pool> (append)",
                 "pack": "move_kernel<from_pool> (save)"}[dominant]
         roof = dict(kernel=name, bound="hbm", achieved=kern[dominant]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=kern[dominant]["gbs"] / HBM_PEAK_GBS, traffic=None)

@@ -260,13 +260,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     auto issue_interior = [&](int tile) {
         const int kt0 = tile * BN;
         const uint32_t stage = __builtin_amdgcn_readfirstlane(lds_offset(ring)) + (uint32_t)((tile % NS) * STAGE);
+        int page_v[NI];                     // all page ids first: one LDS round trip instead of NI
+#pragma unroll
+        for (int i = 0; i < NI; ++i) page_v[i] = pg[(kt0 + ((wave_u + NW * i) % CHUNKS) * KPC) >> 4];
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int cid = wave_u + NW * i;
             const bool is_v = cid >= CHUNKS;
             const int jch = cid % CHUNKS;
             const int t0 = kt0 + jch * KPC;                                 // first key of the chunk
-            const int page = __builtin_amdgcn_readfirstlane(pg[t0 >> 4]);
+            const int page = __builtin_amdgcn_readfirstlane(page_v[i]);
             const uint16_t *base = (is_v ? a.v_pool : a.k_pool) + (((int64_t)page * Hkv + g) * kPageSize + (t0 & 15)) * D;
             dma16_sbase(base, ld_lane_off, stage + (uint32_t)((is_v ? TILE : 0) + jch * CH));
         }
@@ -327,8 +330,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
         const bool has_next = INTERIOR || tile + 1 < n_tiles;
 
         // the stage multiplied in the previous iteration is free: refill it three tiles ahead
-        if (INTERIOR) issue_interior(tile + NS - 1);
-        else if (tile + NS - 1 < n_tiles) issue(tile + NS - 1);
+        // (interior tiles of wavefronts with rows issue a little later, under the first matrix instructions,
+        // where the scalar address arithmetic costs nothing)
+        if (INTERIOR && !LIVE) issue_interior(tile + NS - 1);
+        else if (!INTERIOR && tile + NS - 1 < n_tiles) issue(tile + NS - 1);
         if (has_next) rot_read(st_next);
 
         f32x16 S[MB];
@@ -343,6 +348,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
                 for (int mb = 0; mb < MB; ++mb) {
                     const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + k_rd[mb] + ks * (2 * KPC * 16));
                     S[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[ks], S[mb], 0, 0, 0);
+                }
+                if (INTERIOR && ks == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    issue_interior(tile + NS - 1);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 if (has_next && ks % (KSTEPS / 4) == KSTEPS / 4 - 1) rot_part(st_next, ks / (KSTEPS / 4));
             }
@@ -366,7 +376,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[mb][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            {   // lanes l and l+32 hold the two key halves of one query row: one swap gives both the other half
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
             const bool raise = (mx - m_run) * cscale > 8.0f;
             if (__builtin_amdgcn_ballot_w64(raise) != 0) {
                 const float m_new = raise ? mx : m_run;

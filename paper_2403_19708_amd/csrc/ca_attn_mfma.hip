@@ -385,7 +385,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(AttnArgs a) {
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[mb][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            {   // lanes l and l+32 hold the two key halves of one query row: one swap gives both the other half
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
             const bool raise = (mx - m_run) * cscale > 8.0f;   // also true on the first tile (m_run = -inf)
             if (__builtin_amdgcn_ballot_w64(raise) != 0) {
                 const float m_new = raise ? mx : m_run;

@@ -233,8 +233,8 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
         set_err(err, err_len, "save_mode (0..2) out of range");
         return CA_ERR_INVALID_ARG;
     }
-    if (c->load_mode < 0 || c->load_mode > 2 || c->attn_variant < 0 || c->attn_variant > 2) {
-        set_err(err, err_len, "load_mode (0..2) or attn_variant (0..2) out of range");
+    if (c->load_mode < 0 || c->load_mode > 2 || c->attn_variant < 0 || c->attn_variant > 3) {
+        set_err(err, err_len, "load_mode (0..2) or attn_variant (0..3) out of range");
         return CA_ERR_INVALID_ARG;
     }
     if (c->attn_variant == 2 && c->max_positions > kAttnDmaMaxPositions) {
@@ -954,11 +954,12 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
     a.softmax_scale = softmax_scale;
     int iv;
     CA_HIP(ctx, prof_begin(ctx, kProfAttn, stream, &iv));
+    // 0 picks the LDS-direct kernel whenever its page-id table holds the window
+    const bool direct = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
     if (c.attn_variant == 1) {
         CA_HIP(ctx, launch_attn_ref(a, stream));
-    } else if (c.attn_variant == 2) {
+    } else if (direct) {
         CA_HIP(ctx, launch_attn_dma(a, stream));
-
     } else {
         CA_HIP(ctx, launch_attn_mfma(a, stream));
     }

@@ -131,7 +131,7 @@ def test_save_arbitrary_ranges_bit_exact(case):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [1, 0, 2], ids=["scalar", "mfma", "dma"])
+@pytest.mark.parametrize("variant", [1, 3, 2], ids=["scalar", "staged", "direct"])
 def test_attention_matches_oracle(case, variant):
     run = GpuRun(case, tier="device", attn_variant=variant)
     try:
@@ -150,7 +150,24 @@ def test_attention_matches_oracle(case, variant):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [1, 0, 2], ids=["scalar", "mfma", "dma"])
+@pytest.mark.parametrize("window", [4096, 65536], ids=["direct-by-default", "staged-beyond-32768"])
+def test_default_variant_follows_the_window(window):
+    """attn_variant 0 takes the LDS-direct kernel while its page-id table holds the window and the
+    register-staged kernel beyond; both must give the oracle's result on the same small case."""
+    case = Case([300, 17], [140, 40], [0, 0], 4, 2, 128, seed=23)
+    run = GpuRun(case, tier="device", max_positions=window)
+    try:
+        run.rebase()
+        run.run_layer(0)
+        run.finish()
+        for c in range(case.B):
+            check_contract(run.out_f64(0, c), case.oracle_out(0, c), c)
+            check_tight(run.out_f64(0, c), case.oracle_out(0, c), int(case.n_keep[c]), c)
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("variant", [1, 3, 2], ids=["scalar", "staged", "direct"])
 def test_attention_peaky_softmax(variant):
     """Queries scaled x6: a handful of keys dominate each row and outputs are O(1), so a wrong key,
     a wrong mask edge or a wrong position cannot hide under the tolerance.  Scores grow with the

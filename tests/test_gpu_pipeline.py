@@ -65,7 +65,7 @@ def test_pipeline_orderings_give_identical_bits():
             at += int(case.new_len[c])
 
 
-@pytest.mark.parametrize("variant", [0, 2], ids=["mfma", "dma"])
+@pytest.mark.parametrize("variant", [3, 2], ids=["staged", "direct"])
 def test_both_tile_sizes_agree_with_oracle(variant):
     case = Case([500, 90], [200, 31], [37, 0], 8, 2, 128, seed=52)
     for tile in (128, 256):
@@ -134,7 +134,7 @@ def test_multi_turn_reuse_with_truncation_equals_recompute():
             saved = saved + new
 
 
-@pytest.mark.parametrize("variant", [0, 2], ids=["mfma", "dma"])
+@pytest.mark.parametrize("variant", [3, 2], ids=["staged", "direct"])
 @pytest.mark.parametrize("index", [2, 3, 4, 5])
 def test_full_size_layer_sampled_against_oracle(index, variant):
     """One layer at the benchmark's full shapes and length mix, in the launch configuration the
