@@ -87,6 +87,9 @@ typedef struct {
                              /* kernel, K/V staged through registers (any window)              */
     int32_t attn_tile_rows;  /* stacked query rows per workgroup of the MFMA kernel: 128, 256,  */
                              /* or 0 = choose per batch                                        */
+    int32_t attn_split;      /* 0: when a batch has too few row tiles to keep all compute units */
+                             /* busy, the LDS-direct kernel splits the keys of long tiles over  */
+                             /* several workgroups and merges their shares; 1: never split      */
     int32_t require_load;    /* 1: attention on a layer with kept history that was not loaded */
                              /* under the current plan fails with CA_ERR_NOT_READY            */
     int32_t device;          /* HIP device ordinal                                            */
@@ -146,7 +149,9 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *batch, void *stream);
 /* Copies a piece of the current plan's device metadata to host (synchronises; for tests and
  * debugging).  which: 0 n_keep[n_seqs], 1 cu_q[n_seqs+1], 2 cu_k[n_seqs+1], 3 q_pos[sum new],
  * 4 q_seq[sum new], 5 slot_map[sum context] (page*page_size + slot of every context token),
- * 6 attention work list (4 int32 per item: seq, kv_head, first_row, n_rows; seq -1 = padding).
+ * 6 attention work list (8 int32 per item: seq, kv_head, first_row, n_rows, key_begin, key_end,
+ *   part, 0; seq -1 = padding; part -1 = the item covers all keys its rows see, else the item is
+ *   one share of a row tile whose keys [key_begin, key_end) were split over workgroups).
  * capacity is in int32 elements; *count receives the number written.                         */
 ca_status ca_rebase_read(ca_ctx *ctx, int32_t which, int32_t *out, int64_t capacity, int64_t *count);
 

@@ -39,7 +39,8 @@ class _CConfig(C.Structure):
                 ("rope_base", C.c_float), ("rope_style", C.c_int32), ("pipeline_depth", C.c_int32),
                 ("max_seqs", C.c_int32), ("max_batch_kv_tokens", C.c_int64),
                 ("max_batch_q_tokens", C.c_int64), ("load_mode", C.c_int32), ("save_mode", C.c_int32),
-                ("attn_variant", C.c_int32), ("attn_tile_rows", C.c_int32), ("require_load", C.c_int32),
+                ("attn_variant", C.c_int32), ("attn_tile_rows", C.c_int32), ("attn_split", C.c_int32),
+                ("require_load", C.c_int32),
                 ("device", C.c_int32)]
 
 
@@ -122,6 +123,7 @@ class Config:
     save_mode: int = 0
     attn_variant: int = 0
     attn_tile_rows: int = 0
+    attn_split: int = 0
     require_load: int = 1
     device: int = 0
 
@@ -245,7 +247,7 @@ class Context:
 
     def rebase_read(self, which: int, capacity: int | None = None) -> np.ndarray:
         cap = int(capacity) if capacity is not None else int(
-            max(self.cfg.max_batch_kv_tokens, 8 * (self.cfg.max_batch_q_tokens + 4096)))
+            max(self.cfg.max_batch_kv_tokens, 8 * (self.cfg.max_batch_q_tokens + 16384)))
         out = np.empty(cap, dtype=np.int32)
         cnt = C.c_int64(0)
         self._check(self._lib.ca_rebase_read(self._h, int(which), out.ctypes.data_as(C.POINTER(C.c_int32)),

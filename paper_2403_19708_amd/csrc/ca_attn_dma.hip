@@ -160,8 +160,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     const int Hkv = a.n_kv_heads;
 
     const int row_last = item.row0 + item.n_rows - 1;          // last valid stacked row of the tile
-    const int kmax = n + row_last / G + 1;                      // keys this tile can see
-    const int n_tiles = (kmax + BN - 1) / BN;
+    // keys [key_begin, kmax): what the tile's rows can see, cut to the item's share when the keys of one
+    // row tile are split over several workgroups (key_begin and a cutting key_end are multiples of 64)
+    const int kmax = min(n + row_last / G + 1, item.key_end);
+    const int t_begin = item.key_begin / BN;
+    const int n_tiles = (kmax + BN - 1) / BN;                   // end of the walk (absolute tile index)
 
     // page ids of the visible context -> LDS
     for (int i = tid; i < (kmax + kPageSize - 1) / kPageSize; i += NTHREADS) pg[i] = table[i];
@@ -205,7 +208,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     constexpr int ROT_PARTNER = (PPR / 2) * KPC * 16;
     float2 k_step[8], k_cs[8];
     load_cs<D, STYLE>(a.rope, BN, rot_pr, k_step);
-    load_cs<D, STYLE>(a.rope, rot_active ? rot_kk : 0, rot_pr, k_cs);
+    // first position of this thread's key; a thread whose first key lies past the visible range never sees a
+    // visible one later either, so clamping it is harmless (and keeps the read inside the table)
+    load_cs<D, STYLE>(a.rope, rot_active ? min(t_begin * BN + rot_kk, kmax - 1) : 0, rot_pr, k_cs);
     uint4 kx, ky;
 
     // ---- operand addresses inside a stage ---------------------------------------------------------------
@@ -310,14 +315,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 
     // ---- prologue ---------------------------------------------------------------------------------------
     __syncthreads();                     // page ids are in LDS
-    issue(0);
-    if (n_tiles > 1) issue(1);
-    if (n_tiles > 2) issue(2);
-    if (n_tiles > 2) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }   // tiles 0 and 1 have landed
+    issue(t_begin);
+    if (t_begin + 1 < n_tiles) issue(t_begin + 1);
+    if (t_begin + 2 < n_tiles) issue(t_begin + 2);
+    if (t_begin + 2 < n_tiles) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }   // the first two tiles have landed
     __syncthreads();
-    rot_read(ring);
+    rot_read(ring + (t_begin % NS) * STAGE);
 #pragma unroll
-    for (int w = 0; w < 4; ++w) rot_part(ring, w);
+    for (int w = 0; w < 4; ++w) rot_part(ring + (t_begin % NS) * STAGE, w);
     __syncthreads();
 
     auto walk = [&](int tile, auto interior_tag, auto live_tag) {
@@ -383,7 +388,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
             const bool raise = (mx - m_run) * cscale > 8.0f;
             if (__builtin_amdgcn_ballot_w64(raise) != 0) {
                 const float m_new = raise ? mx : m_run;
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * cscale);
+                // (a row that has not seen a key yet keeps its -inf reference and must not turn 0 * exp2(nan) into nan)
+                const float alpha = raise ? __builtin_amdgcn_exp2f((m_run - m_new) * cscale) : 1.0f;
                 m_run = m_new;
                 l_run *= alpha;
 #pragma unroll
@@ -391,7 +397,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) O[db][i] *= alpha;
             }
-            const float mc = m_run * cscale;
+            // masked tiles: a row that has seen no key so far (possible when the keys are split) has S = -inf
+            // throughout and must get probabilities 0, not exp2(-inf + inf)
+            const float mc = (!INTERIOR && m_run == -INFINITY) ? 0.f : m_run * cscale;
             float psum = 0.f;
 #pragma unroll
             for (int ks2 = 0; ks2 < KS2; ++ks2) {
@@ -429,8 +437,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     };
 
     const int first_qpos = n + item.row0 / G;
-    const int n_interior = max(0, min((first_qpos + 1) / BN, kmax / BN - NS));
-    int tile = 0;
+    const int n_interior = max(t_begin, min((first_qpos + 1) / BN, kmax / BN - NS));   // end of the interior tiles
+    int tile = t_begin;
     if (wave_live) {
         for (; tile < n_interior; ++tile) walk(tile, std::true_type{}, std::true_type{});
         for (; tile < n_tiles; ++tile) walk(tile, std::false_type{}, std::true_type{});
@@ -441,6 +449,27 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 
     // ---- epilogue: normalise and store --------------------------------------------------------------
     const float l_all = l_run + __shfl_xor(l_run, 32);
+    if (item.part >= 0) {
+        // keys split over several workgroups: leave the unnormalised sums, the reference maximum and the
+        // denominator of this share in the scratch buffer; combine_kernel merges the shares
+        if (row_valid) {
+            const int rt = r - item.row0;                       // row inside the tile
+            float *base = a.partial + (int64_t)item.part * a.tile_rows * (D + 2);
+            float *prow = base + (int64_t)rt * D;
+#pragma unroll
+            for (int db = 0; db < DBLKS; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const int d = 32 * db + i4 * 8 + half * 4;
+                    *reinterpret_cast<float4 *>(prow + d) = make_float4(O[db][4 * i4], O[db][4 * i4 + 1], O[db][4 * i4 + 2], O[db][4 * i4 + 3]);
+                }
+            if (half == 0) {
+                base[(int64_t)a.tile_rows * D + rt] = m_run;
+                base[(int64_t)a.tile_rows * (D + 1) + rt] = l_all;
+            }
+        }
+        return;
+    }
     if (row_valid) {
         const float inv = 1.f / l_all;
         uint16_t *orow = a.out + ((int64_t)(q0 + j) * a.n_q_heads + head) * D;
@@ -455,6 +484,52 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
                 *reinterpret_cast<uint2 *>(orow + d) = o;
             }
     }
+}
+
+// Merges the shares of row tiles whose keys were split (Section 2.1's softmax over the union of the key
+// ranges): with M = max_s m_s and w_s = exp2((m_s - M) * c), out = sum_s w_s O_s / sum_s w_s l_s.
+// blockIdx.x = split row tile, blockIdx.y = group of 256 / (D/4) rows; a thread owns four head dimensions of
+// one row and has the loads of all shares in flight at once.
+__global__ __launch_bounds__(256) void combine_kernel(AttnArgs a) {
+    const CombineItem ci = a.combine[blockIdx.x];
+    const int D = a.head_dim;
+    const int vec_per_row = D / 4;
+    const int rt = blockIdx.y * (256 / vec_per_row) + threadIdx.x / vec_per_row;
+    if (rt >= ci.n_rows) return;
+    const int d = 4 * (threadIdx.x % vec_per_row);
+    const int G = a.n_q_heads / a.n_kv_heads;
+    const float cscale = a.softmax_scale * 1.4426950408889634f;
+    const int64_t part_stride = (int64_t)a.tile_rows * (D + 2);
+    const float *first = a.partial + ci.first_part * part_stride;
+    float m[kAttnMaxPartsPerTile], l[kAttnMaxPartsPerTile];
+    float4 o[kAttnMaxPartsPerTile];
+#pragma unroll
+    for (int s = 0; s < kAttnMaxPartsPerTile; ++s) {
+        const bool on = s < ci.n_parts;
+        const float *base = first + (on ? s : 0) * part_stride;
+        m[s] = on ? base[(int64_t)a.tile_rows * D + rt] : -INFINITY;
+        l[s] = base[(int64_t)a.tile_rows * (D + 1) + rt];
+        o[s] = *reinterpret_cast<const float4 *>(base + (int64_t)rt * D + d);
+    }
+    float M = m[0];
+#pragma unroll
+    for (int s = 1; s < kAttnMaxPartsPerTile; ++s) M = fmaxf(M, m[s]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lsum = 0.f;
+#pragma unroll
+    for (int s = 0; s < kAttnMaxPartsPerTile; ++s) {
+        const float w = (m[s] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m[s] - M) * cscale);
+        acc.x += w * o[s].x; acc.y += w * o[s].y; acc.z += w * o[s].z; acc.w += w * o[s].w;
+        lsum += w * l[s];
+    }
+    const float inv = 1.f / lsum;
+    const int r = ci.row0 + rt;
+    const int j = r / G;
+    const int head = ci.kv_head * G + (r - j * G);
+    uint2 ob;
+    ob.x = pack_bf16(acc.x * inv, acc.y * inv);
+    ob.y = pack_bf16(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<uint2 *>(a.out + ((int64_t)(a.cu_q[ci.seq] + j) * a.n_q_heads + head) * D + d) = ob;
 }
 
 template <int NW, int BN>
@@ -477,9 +552,15 @@ hipError_t launch_shape(const AttnArgs &a, hipStream_t stream) {
 
 hipError_t launch_attn_dma(const AttnArgs &a, hipStream_t stream) {
     if (a.n_items <= 0) return hipSuccess;
-    if (a.tile_rows == 256) return launch_shape<8, 64>(a, stream);
-    if (a.tile_rows == 128) return launch_shape<4, 32>(a, stream);
-    return hipErrorInvalidValue;
+    if (a.n_combine > 0 && (a.partial == nullptr || a.combine == nullptr)) return hipErrorInvalidValue;
+    hipError_t e;
+    if (a.tile_rows == 256) e = launch_shape<8, 64>(a, stream);
+    else if (a.tile_rows == 128) e = launch_shape<4, 32>(a, stream);
+    else return hipErrorInvalidValue;
+    if (e != hipSuccess || a.n_combine <= 0) return e;
+    const int rows_per_group = 256 / (a.head_dim / 4);
+    hipLaunchKernelGGL(combine_kernel, dim3(a.n_combine, (a.tile_rows + rows_per_group - 1) / rows_per_group), dim3(256), 0, stream, a);
+    return hipGetLastError();
 }
 
 }  // namespace ca

@@ -63,6 +63,16 @@ struct WorkItem {      // one tile of stacked query rows of one (conversation, k
     int32_t kv_head;
     int32_t row0;      // first stacked row; row r <-> new token r / G, query head kv_head*G + r % G
     int32_t n_rows;
+    int32_t key_begin; // the item's share of the keys: [key_begin, min(key_end, what its rows see));
+    int32_t key_end;   // the whole range unless the row tile was split; cuts are multiples of 64
+    int32_t part;      // -1: the item writes `out`; else index of its share in the partial-result buffer
+    int32_t reserved;
+};
+
+struct CombineItem {   // a row tile whose keys were split: shares first_part .. first_part + n_parts - 1
+    int32_t seq, kv_head, row0, n_rows;
+    int32_t first_part, n_parts;
+    int32_t reserved[2];
 };
 
 struct AttnArgs {
@@ -76,8 +86,12 @@ struct AttnArgs {
     const int32_t *q_pos;    // [total_q] rebased position of every new token
     const int32_t *q_seq;    // [total_q] its conversation
     const WorkItem *items;
+    const CombineItem *combine;   // row tiles to merge after the walk (n_combine of them)
+    float *partial;          // shares of split row tiles: per part [tile_rows][head_dim] sums, [tile_rows] maxima,
+                             // [tile_rows] denominators (fp32)
     const float2 *rope;      // [max_positions][head_dim/2] (cos, sin)
     int32_t n_items;
+    int32_t n_combine;
     int32_t total_q;
     int32_t max_pages;
     int32_t n_q_heads, n_kv_heads, head_dim;
@@ -93,5 +107,8 @@ hipError_t launch_attn_mfma(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_ref(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_dma(const AttnArgs &args, hipStream_t stream);
 constexpr int kAttnDmaMaxPositions = 32768;   // page ids of one conversation are kept in LDS
+constexpr int kAttnMaxParts = 1024;           // shares of split row tiles per batch (sizes the partial-result buffer)
+constexpr int kAttnMaxPartsPerTile = 16;
+constexpr int kAttnMinPartKeys = 256;         // a share is at least this many keys
 
 }  // namespace ca

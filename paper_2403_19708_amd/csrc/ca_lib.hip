@@ -34,11 +34,14 @@ struct ca_ctx {
     hipEvent_t ev_join[3] = {nullptr, nullptr, nullptr};
     bool meta_in_flight = false;
     // offsets (bytes) inside the metadata image
-    size_t off_table = 0, off_n_keep = 0, off_cu_q = 0, off_cu_k = 0, off_items = 0, off_q_pos = 0,
+    size_t off_table = 0, off_n_keep = 0, off_cu_q = 0, off_cu_k = 0, off_items = 0, off_combine = 0, off_q_pos = 0,
            off_q_seq = 0, off_slot_map = 0, upload_bytes = 0;
+    size_t items_capacity = 0;         // work items the image has room for
+    float *partial = nullptr;          // shares of row tiles whose keys were split over workgroups
+    int32_t n_cus = 256;               // compute units of the device (balancing target)
     // current plan (host copies)
     bool has_plan = false;
-    int32_t n_seqs = 0, max_pages = 0, num_pages = 0, n_items = 0, tile_rows = 128;
+    int32_t n_seqs = 0, max_pages = 0, num_pages = 0, n_items = 0, n_combine = 0, tile_rows = 128;
     int64_t total_q = 0, total_k = 0, total_n = 0;
     std::vector<int32_t> hist_len, keep_start, new_len, n_keep, cu_q, cu_k;
     std::vector<int64_t> cu_n;
@@ -182,6 +185,7 @@ void ca_config_default(ca_config *c) {
     c->save_mode = 0;
     c->attn_variant = 0;
     c->attn_tile_rows = 0;
+    c->attn_split = 0;
     c->require_load = 1;
     c->device = 0;
 }
@@ -245,6 +249,7 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
         set_err(err, err_len, "attn_tile_rows %d unsupported (0, 128 or 256)", c->attn_tile_rows);
         return CA_ERR_UNSUPPORTED;
     }
+    if (c->attn_split < 0 || c->attn_split > 1) { set_err(err, err_len, "attn_split must be 0 or 1"); return CA_ERR_INVALID_ARG; }
     if (c->device < 0) { set_err(err, err_len, "device < 0"); return CA_ERR_INVALID_ARG; }
     return CA_OK;
 }
@@ -366,6 +371,7 @@ void ca_destroy(ca_ctx *ctx) {
     if (ctx->load_slots) (void)hipFree(ctx->load_slots);
     if (ctx->save_slots) (void)hipFree(ctx->save_slots);
     if (ctx->rope) (void)hipFree(ctx->rope);
+    if (ctx->partial) (void)hipFree(ctx->partial);
     if (ctx->d_meta) (void)hipFree(ctx->d_meta);
     if (ctx->h_meta) (void)hipHostFree(ctx->h_meta);
     if (ctx->s_copy) (void)hipStreamDestroy(ctx->s_copy);
@@ -428,13 +434,16 @@ static ca_status create_impl(ca_ctx *ctx) {
         const size_t units = (size_t)c.max_seqs * c.n_kv_heads;
         const size_t g = (size_t)c.n_q_heads / c.n_kv_heads;
         // tiles: sum over units of ceil(rows/tile) <= total_q*g*n_kv_heads/tile + units, padded per die
-        const size_t max_items = (size_t)c.max_batch_q_tokens * g * c.n_kv_heads / kAttnTileRowsMin + units;
+        // (+ the extra items that splitting keys can add)
+        const size_t max_items = (size_t)c.max_batch_q_tokens * g * c.n_kv_heads / kAttnTileRowsMin + units + kAttnMaxParts;
         const size_t max_items_padded = (max_items + 1) * kXcds;  // worst case: every tile on one die
+        ctx->items_capacity = max_items_padded;
         size_t off = 0;
         ctx->off_table = off;   off = align_up(off + (size_t)c.max_seqs * max_cols * 4, 256);
         ctx->off_n_keep = off;  off = align_up(off + (size_t)c.max_seqs * 4, 256);
         ctx->off_cu_q = off;    off = align_up(off + ((size_t)c.max_seqs + 1) * 4, 256);
         ctx->off_cu_k = off;    off = align_up(off + ((size_t)c.max_seqs + 1) * 4, 256);
+        ctx->off_combine = off; off = align_up(off + (size_t)kAttnMaxParts * sizeof(CombineItem), 256);
         ctx->off_items = off;   off = align_up(off + max_items_padded * sizeof(WorkItem), 256);
         ctx->upload_bytes = off;
         ctx->off_q_pos = off;   off = align_up(off + (size_t)c.max_batch_q_tokens * 4, 256);
@@ -443,6 +452,17 @@ static ca_status create_impl(ca_ctx *ctx) {
         ctx->meta_bytes = off;
         CA_HIP(ctx, hipMalloc((void **)&ctx->d_meta, ctx->meta_bytes));
         CA_HIP(ctx, hipHostMalloc((void **)&ctx->h_meta, ctx->upload_bytes, hipHostMallocDefault));
+    }
+    // Partial results of row tiles whose keys are split over workgroups (only the LDS-direct kernel splits).
+    const bool may_split = c.attn_split == 0 && (c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions));
+    if (may_split) {
+        const size_t bytes = (size_t)kAttnMaxParts * 256 * (size_t)(c.head_dim + 2) * sizeof(float);
+        CA_HIP(ctx, hipMalloc((void **)&ctx->partial, bytes));
+    }
+    {
+        hipDeviceProp_t prop;
+        CA_HIP(ctx, hipGetDeviceProperties(&prop, c.device));
+        ctx->n_cus = std::max(8, prop.multiProcessorCount);
     }
     return CA_OK;
 }
@@ -555,6 +575,7 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
             tile = most > 128 ? 256 : 128;
         }
         ctx->tile_rows = tile;
+        const bool direct_kernel = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
         struct Unit { int32_t seq, head; int64_t work; };
         std::vector<Unit> units;
         units.reserve((size_t)B * c.n_kv_heads);
@@ -569,32 +590,107 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
         // a unit with more tiles than a die's fair share is cut into chunks so that a small batch
         // still spreads over all dies
         const int chunk_cap = (int)std::max<int64_t>(1, (total_tiles + kXcds - 1) / kXcds);
-        std::vector<std::vector<WorkItem>> per_die(kXcds);
-        int64_t load[kXcds] = {0};
+        // Cost of an item in the time a full workgroup needs for one 64-key tile (measured on single items:
+        // a 256-row workgroup whose rows fill at most four wavefronts, one per SIMD, takes 0.72 of that per
+        // tile; rotating Q, filling the load pipeline and the epilogue cost about three tiles).
+        struct Item { WorkItem w; double cost; int32_t parent; };
+        auto item_cost = [&](int n_rows, int keys) {
+            const double per_tile = (tile == 256 && n_rows <= 128) ? 0.72 : 1.0;
+            return per_tile * ((keys + 63) / 64) + 3.0;
+        };
+        std::vector<std::vector<Item>> per_die(kXcds);
+        double load[kXcds] = {0};
+        int32_t n_parents = 0;
         for (const Unit &u : units) {
             const int rows = b->new_len[u.seq] * G;
             const int n_tiles = (rows + tile - 1) / tile;
-            const int64_t n = ctx->n_keep[u.seq];
+            const int n = ctx->n_keep[u.seq];
             for (int hi = n_tiles; hi > 0; hi -= chunk_cap) {  // later rows see more keys: longest first
                 const int lo = std::max(0, hi - chunk_cap);
                 int die = 0;
                 for (int d = 1; d < kXcds; ++d) if (load[d] < load[die]) die = d;
                 for (int t = hi - 1; t >= lo; --t) {
                     const int n_rows = std::min(tile, rows - t * tile);
-                    load[die] += (int64_t)n_rows * (n + (t * tile + n_rows - 1) / G + 1);
-                    per_die[die].push_back({u.seq, u.head, t * tile, n_rows});
+                    const int keys = n + (t * tile + n_rows - 1) / G + 1;       // what the tile's rows see
+                    const double cost = item_cost(n_rows, keys);
+                    load[die] += cost;
+                    per_die[die].push_back({WorkItem{u.seq, u.head, t * tile, n_rows, 0, keys, -1, 0}, cost, n_parents++});
                 }
             }
         }
+
+        // Few, long items leave compute units idle at the end (or, for a small batch, from the start): split
+        // the keys of the longest items over several workgroups until a longest-first schedule of the die's
+        // items over its compute units is within 12 % of the ideal.  Shares are merged by combine_kernel.
+        size_t n_live = 0;
+        for (auto &v : per_die) n_live += v.size();
+        std::vector<int32_t> parts_of(n_parents, 1);
+        int32_t n_split_parts = 0;          // shares that need a slot in the partial-result buffer
+        if (ctx->partial && direct_kernel && n_live < (size_t)6 * ctx->n_cus) {
+            const int bins = std::max(1, ctx->n_cus / kXcds) * (tile == 128 ? 2 : 1);
+            std::vector<double> bin(bins);
+            for (int d = 0; d < kXcds; ++d) {
+                auto &v = per_die[d];
+                for (int iter = 0; iter < 4 * bins && !v.empty(); ++iter) {
+                    std::stable_sort(v.begin(), v.end(), [](const Item &x, const Item &y) { return x.cost > y.cost; });
+                    std::fill(bin.begin(), bin.end(), 0.0);
+                    double total = 0;
+                    for (const Item &it : v) { *std::min_element(bin.begin(), bin.end()) += it.cost; total += it.cost; }
+                    const double makespan = *std::max_element(bin.begin(), bin.end());
+                    if (makespan <= 1.12 * total / bins + 1.0) break;   // (cutting further was measured to cost more than it gains)
+                    size_t pick = v.size();
+                    for (size_t k = 0; k < v.size(); ++k) {      // the longest item that may still be cut
+                        const Item &it = v[k];
+                        const int len = it.w.key_end - it.w.key_begin;
+                        const int extra = parts_of[it.parent] == 1 ? 2 : 1;   // slots a cut of this item adds
+                        if (len >= 2 * kAttnMinPartKeys && parts_of[it.parent] < kAttnMaxPartsPerTile &&
+                            n_split_parts + extra <= kAttnMaxParts) { pick = k; break; }
+                    }
+                    if (pick == v.size()) break;
+                    Item lo_half = v[pick], hi_half = v[pick];
+                    const int tiles64 = (lo_half.w.key_end - lo_half.w.key_begin + 63) / 64;
+                    const int mid = lo_half.w.key_begin + (tiles64 / 2) * 64;
+                    lo_half.w.key_end = mid;
+                    hi_half.w.key_begin = mid;
+                    lo_half.cost = item_cost(lo_half.w.n_rows, mid - lo_half.w.key_begin);
+                    hi_half.cost = item_cost(hi_half.w.n_rows, hi_half.w.key_end - mid);
+                    n_split_parts += parts_of[lo_half.parent] == 1 ? 2 : 1;
+                    parts_of[lo_half.parent] += 1;
+                    v[pick] = lo_half;
+                    v.push_back(hi_half);
+                }
+                std::stable_sort(v.begin(), v.end(), [](const Item &x, const Item &y) { return x.cost > y.cost; });
+            }
+        }
+        // number the shares of split row tiles consecutively and list the tiles for the merge
+        CombineItem *combine = (CombineItem *)(ctx->h_meta + ctx->off_combine);
+        int32_t n_combine = 0;
+        {
+            std::vector<int32_t> first_part(n_parents, -1), next_part(n_parents, 0);
+            int32_t at = 0;
+            for (auto &v : per_die)
+                for (Item &it : v) {
+                    if (parts_of[it.parent] == 1) continue;
+                    if (first_part[it.parent] < 0) {
+                        first_part[it.parent] = at;
+                        at += parts_of[it.parent];
+                        combine[n_combine++] = CombineItem{it.w.seq, it.w.kv_head, it.w.row0, it.w.n_rows,
+                                                           first_part[it.parent], parts_of[it.parent], {0, 0}};
+                    }
+                    it.w.part = first_part[it.parent] + next_part[it.parent]++;
+                }
+            if (at != n_split_parts || at > kAttnMaxParts) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_rope_rebase: internal: %d shares numbered, %d planned", at, n_split_parts);
+        }
+        ctx->n_combine = n_combine;
+
         size_t longest = 0;
         for (auto &v : per_die) longest = std::max(longest, v.size());
         const size_t n_items = longest * kXcds;
-        const size_t cap = (ctx->upload_bytes - ctx->off_items) / sizeof(WorkItem);
-        if (n_items > cap) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_rope_rebase: %zu work items exceed capacity %zu", n_items, cap);
+        if (n_items > ctx->items_capacity) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_rope_rebase: %zu work items exceed capacity %zu", n_items, ctx->items_capacity);
         WorkItem *items = (WorkItem *)(ctx->h_meta + ctx->off_items);
         for (size_t s = 0; s < longest; ++s)
             for (int d = 0; d < kXcds; ++d)
-                items[s * kXcds + d] = s < per_die[d].size() ? per_die[d][s] : WorkItem{-1, 0, 0, 0};
+                items[s * kXcds + d] = s < per_die[d].size() ? per_die[d][s].w : WorkItem{-1, 0, 0, 0, 0, 0, -1, 0};
         ctx->n_items = (int32_t)n_items;
     }
 
@@ -642,7 +738,7 @@ ca_status ca_rebase_read(ca_ctx *ctx, int32_t which, int32_t *out, int64_t capac
         case 3: off = ctx->off_q_pos; n = ctx->total_q; break;
         case 4: off = ctx->off_q_seq; n = ctx->total_q; break;
         case 5: off = ctx->off_slot_map; n = ctx->total_k; break;
-        case 6: off = ctx->off_items; n = (int64_t)ctx->n_items * 4; break;
+        case 6: off = ctx->off_items; n = (int64_t)ctx->n_items * 8; break;
         default: return fail(ctx, CA_ERR_INVALID_ARG, "ca_rebase_read: which = %d", which);
     }
     if (n > capacity) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_rebase_read: need %lld elements, capacity %lld", (long long)n, (long long)capacity);
@@ -942,6 +1038,9 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
     a.q_pos = (const int32_t *)(ctx->d_meta + ctx->off_q_pos);
     a.q_seq = (const int32_t *)(ctx->d_meta + ctx->off_q_seq);
     a.items = (const WorkItem *)(ctx->d_meta + ctx->off_items);
+    a.combine = (const CombineItem *)(ctx->d_meta + ctx->off_combine);
+    a.partial = ctx->partial;
+    a.n_combine = ctx->n_combine;
     a.rope = ctx->rope;
     a.n_items = ctx->n_items;
     a.total_q = (int32_t)ctx->total_q;

@@ -65,13 +65,26 @@ def test_rebase_metadata_bit_exact(case):
         for which, key in enumerate(["n_keep", "cu_q", "cu_k", "q_pos", "q_seq", "slot_map"]):
             got = run.ctx.rebase_read(which)
             assert np.array_equal(got, want[key]), key
-        items = run.ctx.rebase_read(6).reshape(-1, 4)
+        items = run.ctx.rebase_read(6).reshape(-1, 8)
         live = items[items[:, 0] >= 0]
         G = case.n_q_heads // case.n_kv_heads
-        # every stacked row of every (conversation, kv head) is covered exactly once
-        cover = {}
-        for seq, head, row0, n_rows in live:
+        # every stacked row of every (conversation, kv head) is covered exactly once, and where the keys of
+        # a row tile are split over several items their shares tile [0, keys the rows see) without gaps
+        cover, shares = {}, {}
+        for seq, head, row0, n_rows, k0, k1, part, _ in live:
+            shares.setdefault((seq, head, row0, n_rows), []).append((k0, k1, part))
+        for (seq, head, row0, n_rows), parts in shares.items():
             cover.setdefault((seq, head), []).append((row0, n_rows))
+            parts.sort()
+            sees = int(case.n_keep[seq]) + (row0 + n_rows - 1) // G + 1
+            assert parts[0][0] == 0 and parts[-1][1] >= sees
+            for (a0, a1, pa), (b0, b1, pb) in zip(parts, parts[1:]):
+                assert a1 == b0 and a1 % 64 == 0 and b1 - b0 >= 256 and a1 - a0 >= 256
+            if len(parts) == 1:
+                assert parts[0][2] == -1
+            else:
+                ids = sorted(p for _, _, p in parts)
+                assert ids[0] >= 0 and ids == list(range(ids[0], ids[0] + len(parts)))
         assert len(cover) == case.B * case.n_kv_heads
         for (seq, head), tiles in cover.items():
             tiles.sort()
@@ -146,6 +159,33 @@ def test_attention_matches_oracle(case, variant):
             check_contract(got, want, c)
             check_tight(got, want, case.n_keep[c], c)
         print(f"variant {variant}: worst max-abs {worst[0]:.2e} mean-abs {worst[1]:.2e}")
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("split", [0, 1], ids=["split", "whole"])
+@pytest.mark.parametrize("shape", [(4, 2, 128, 0), (8, 1, 64, 1)], ids=["gqa2-d128", "gqa8-d64-interleaved"])
+def test_small_batch_splits_keys_over_workgroups(shape, split):
+    """One or two conversations with a long history are far too few row tiles for 256 compute units: the
+    planner cuts the keys of each tile into shares for several workgroups and a second kernel merges
+    them.  The result must not depend on it (attn_split = 1 switches the cutting off), truncation and a
+    ragged tail included."""
+    hq, hkv, d, style = shape
+    case = Case([3000, 700], [70, 9], [123, 0], hq, hkv, d, seed=31, style=style)
+    run = GpuRun(case, tier="device", attn_split=split)
+    try:
+        run.rebase()
+        items = run.ctx.rebase_read(6).reshape(-1, 8)
+        shares = items[(items[:, 0] >= 0) & (items[:, 6] >= 0)]
+        if split == 0:
+            assert len(shares) >= 8 and shares[:, 6].max() == len(shares) - 1     # really split, slots dense
+        else:
+            assert len(shares) == 0
+        run.run_layer(0)
+        run.finish()
+        for c in range(case.B):
+            check_contract(run.out_f64(0, c), case.oracle_out(0, c), c)
+            check_tight(run.out_f64(0, c), case.oracle_out(0, c), int(case.n_keep[c]), c)
     finally:
         run.close()
 
