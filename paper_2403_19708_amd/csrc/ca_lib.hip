@@ -11,6 +11,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <new>
 #include <string>
 #include <vector>
@@ -622,44 +623,55 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
         // Few, long items leave compute units idle at the end (or, for a small batch, from the start): split
         // the keys of the longest items over several workgroups until a longest-first schedule of the die's
         // items over its compute units is within 12 % of the ideal.  Shares are merged by combine_kernel.
+        // Up to four rounds per die; a round halves every item longer than 0.7 of the ideal load of a
+        // compute unit (so 16 shares per row tile at most).
         size_t n_live = 0;
         for (auto &v : per_die) n_live += v.size();
         std::vector<int32_t> parts_of(n_parents, 1);
         int32_t n_split_parts = 0;          // shares that need a slot in the partial-result buffer
+        const auto by_cost = [](const Item &x, const Item &y) { return x.cost > y.cost; };
         if (ctx->partial && direct_kernel && n_live < (size_t)6 * ctx->n_cus) {
             const int bins = std::max(1, ctx->n_cus / kXcds) * (tile == 128 ? 2 : 1);
-            std::vector<double> bin(bins);
+            std::vector<double> heap;
             for (int d = 0; d < kXcds; ++d) {
                 auto &v = per_die[d];
-                for (int iter = 0; iter < 4 * bins && !v.empty(); ++iter) {
-                    std::stable_sort(v.begin(), v.end(), [](const Item &x, const Item &y) { return x.cost > y.cost; });
-                    std::fill(bin.begin(), bin.end(), 0.0);
+                for (int round = 0; round < 4 && !v.empty(); ++round) {
+                    std::stable_sort(v.begin(), v.end(), by_cost);
+                    // longest-first list schedule over `bins` compute units (min-heap of their loads)
+                    heap.assign(bins, 0.0);
                     double total = 0;
-                    for (const Item &it : v) { *std::min_element(bin.begin(), bin.end()) += it.cost; total += it.cost; }
-                    const double makespan = *std::max_element(bin.begin(), bin.end());
-                    if (makespan <= 1.12 * total / bins + 1.0) break;   // (cutting further was measured to cost more than it gains)
-                    size_t pick = v.size();
-                    for (size_t k = 0; k < v.size(); ++k) {      // the longest item that may still be cut
-                        const Item &it = v[k];
+                    for (const Item &it : v) {
+                        std::pop_heap(heap.begin(), heap.end(), std::greater<double>());
+                        heap.back() += it.cost;
+                        std::push_heap(heap.begin(), heap.end(), std::greater<double>());
+                        total += it.cost;
+                    }
+                    const double makespan = *std::max_element(heap.begin(), heap.end());
+                    const double ideal = total / bins;
+                    if (makespan <= 1.12 * ideal + 1.0) break;   // (cutting further was measured to cost more than it gains)
+                    const size_t n_before = v.size();
+                    bool cut_any = false;
+                    for (size_t k = 0; k < n_before && v[k].cost > 0.7 * ideal; ++k) {
+                        Item &it = v[k];
                         const int len = it.w.key_end - it.w.key_begin;
                         const int extra = parts_of[it.parent] == 1 ? 2 : 1;   // slots a cut of this item adds
-                        if (len >= 2 * kAttnMinPartKeys && parts_of[it.parent] < kAttnMaxPartsPerTile &&
-                            n_split_parts + extra <= kAttnMaxParts) { pick = k; break; }
+                        if (len < 2 * kAttnMinPartKeys || parts_of[it.parent] >= kAttnMaxPartsPerTile ||
+                            n_split_parts + extra > kAttnMaxParts) continue;
+                        Item hi_half = it;
+                        const int tiles64 = (len + 63) / 64;
+                        const int mid = it.w.key_begin + (tiles64 / 2) * 64;
+                        it.w.key_end = mid;
+                        hi_half.w.key_begin = mid;
+                        it.cost = item_cost(it.w.n_rows, mid - it.w.key_begin);
+                        hi_half.cost = item_cost(hi_half.w.n_rows, hi_half.w.key_end - mid);
+                        n_split_parts += extra;
+                        parts_of[it.parent] += 1;
+                        v.push_back(hi_half);          // (invalidates `it`)
+                        cut_any = true;
                     }
-                    if (pick == v.size()) break;
-                    Item lo_half = v[pick], hi_half = v[pick];
-                    const int tiles64 = (lo_half.w.key_end - lo_half.w.key_begin + 63) / 64;
-                    const int mid = lo_half.w.key_begin + (tiles64 / 2) * 64;
-                    lo_half.w.key_end = mid;
-                    hi_half.w.key_begin = mid;
-                    lo_half.cost = item_cost(lo_half.w.n_rows, mid - lo_half.w.key_begin);
-                    hi_half.cost = item_cost(hi_half.w.n_rows, hi_half.w.key_end - mid);
-                    n_split_parts += parts_of[lo_half.parent] == 1 ? 2 : 1;
-                    parts_of[lo_half.parent] += 1;
-                    v[pick] = lo_half;
-                    v.push_back(hi_half);
+                    if (!cut_any) break;
                 }
-                std::stable_sort(v.begin(), v.end(), [](const Item &x, const Item &y) { return x.cost > y.cost; });
+                std::stable_sort(v.begin(), v.end(), by_cost);
             }
         }
         // number the shares of split row tiles consecutively and list the tiles for the merge
