@@ -97,16 +97,23 @@ typedef struct {
 
 /* One batch of conversations about to run a new turn.  All pointers are HOST memory and are
  * read during ca_rope_rebase only.  keep_start[c] in [0, hist_len[c]] is the first saved token
- * that survives truncation; n_keep = hist_len - keep_start; context = n_keep + new_len.       */
+ * that survives truncation; n_keep = hist_len - keep_start; context = n_keep + new_len.
+ * A token discarding list (Section 3.4, last paragraph) is given as its complement: the kept
+ * saved tokens of conversation c are the union of keep_range_count[c] ranges [begin, end) taken
+ * in order from keep_ranges; inside a conversation the ranges are non-empty, increasing and
+ * disjoint, inside [0, hist_len[c]].  n_keep is then the sum of their lengths, the kept tokens
+ * are renumbered densely from 0 in that order, and keep_start is not read.                     */
 typedef struct {
     int32_t n_seqs;
     const int32_t *hist_len;    /* [n_seqs] tokens saved in the host tier                     */
-    const int32_t *keep_start;  /* [n_seqs]                                                   */
+    const int32_t *keep_start;  /* [n_seqs]; may be NULL when keep_ranges is given            */
     const int32_t *new_len;     /* [n_seqs] >= 1                                              */
     const int32_t *block_table; /* [n_seqs][max_pages]; the first ceil(context/page_size)     */
                                 /* entries of a row must be distinct valid pages              */
     int32_t max_pages;
     int32_t num_pages;          /* pages in every pool later passed with this batch           */
+    const int32_t *keep_ranges;       /* NULL, or [sum keep_range_count][2] (begin, end)      */
+    const int32_t *keep_range_count;  /* NULL iff keep_ranges is NULL; [n_seqs], each >= 0    */
 } ca_batch;
 
 /* ---- context ------------------------------------------------------------------------ */
@@ -137,6 +144,17 @@ const char *ca_status_string(ca_status s);
 ca_status ca_truncate_plan(const int32_t *hist_len, const int32_t *new_len, int32_t window,
                            double ratio, int32_t policy, int32_t n, int32_t *keep_start_out);
 
+/* The same overflow rule as policy 0, with a discarding list that spares the first n_sink saved
+ * tokens (Section 3.4: "selective preservation", e.g. the initial tokens): without overflow
+ * conversation c keeps one range [0, hist_len); on overflow it keeps floor(window*(1-ratio)) -
+ * new_len history tokens (0 if negative): the first min(n_sink, that many) and the most recent
+ * rest.  ranges_out: [n][2][2] (two (begin, end) slots per conversation, unused ones 0, 0);
+ * count_out[c] in {0, 1, 2}; adjacent pieces are merged into one range.  To pass the result as
+ * ca_batch.keep_ranges, compact the used slots in order.                                      */
+ca_status ca_truncate_plan_sinks(const int32_t *hist_len, const int32_t *new_len, int32_t window,
+                                 double ratio, int32_t n_sink, int32_t n, int32_t *ranges_out,
+                                 int32_t *count_out);
+
 /* ---- Section 3.4: position rebasing --------------------------------------------------- */
 /* Makes `batch` the context's current plan: numbers the kept tokens of every conversation
  * from 0 (keys 0..context-1, new token j at n_keep + j), and builds on the device the
@@ -158,8 +176,9 @@ ca_status ca_rebase_read(ca_ctx *ctx, int32_t which, int32_t *out, int64_t capac
 /* ---- Section 3.2.1: layer-wise loading -------------------------------------------------- */
 /* Brings the kept history of `layer` into the pools: for every conversation c the tokens
  * [keep_start[c], hist_len[c]) of src_k[c] / src_v[c] (contiguous layout, pointer to saved
- * token 0 of this layer; host array of n_seqs pointers) become context tokens [0, n_keep[c]).
- * Truncation is just the source offset.  Runs on the internal copy-in and unpack streams and
+ * token 0 of this layer; host array of n_seqs pointers) -- or, with a discarding list, the
+ * tokens of its kept ranges in order -- become context tokens [0, n_keep[c]).
+ * Truncation and discarding are just source offsets.  Runs on the internal copy-in and unpack streams and
  * marks the layer ready; ca_cached_prefill_attn(layer) waits for that mark on its own stream.
  * Sources: pinned host memory (staged hipMemcpyAsync into a ring slot + unpack kernel, or read
  * in place by the unpack kernel, see load_mode) or device memory (read in place).  A layer can

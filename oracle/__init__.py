@@ -8,6 +8,8 @@ from .ca_oracle import (  # noqa: F401
     attention_positions,
     build,
     cached_attention,
+    cached_attention_kept,
+    kept_indices_sinks,
     kv_bytes_per_token,
     n_threads,
     pack,

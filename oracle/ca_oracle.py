@@ -141,6 +141,33 @@ def cached_attention(Kh, Vh, Qn, Kn, Vn, keep_start: int = 0, base=10000.0, styl
     return (O, P) if return_probs else O
 
 
+def cached_attention_kept(Kh, Vh, kept, Qn, Kn, Vn, **kw):
+    """Section 3.4, last paragraph: the history survives a token discarding list as the saved tokens with
+    indices `kept` (increasing).  The store delivers exactly those, they are renumbered densely from 0 and
+    the new turn attends to them: by definition the reuse path over the pruned history."""
+    kept = np.asarray(kept, dtype=np.int64)
+    assert kept.ndim == 1 and (len(kept) < 2 or np.all(np.diff(kept) > 0))
+    assert len(kept) == 0 or (kept[0] >= 0 and kept[-1] < np.asarray(Kh).shape[0])
+    return cached_attention(np.asarray(Kh)[kept], np.asarray(Vh)[kept], Qn, Kn, Vn, keep_start=0, **kw)
+
+
+def kept_indices_sinks(hist_len, new_len, window: int, ratio: float = 0.5, n_sink: int = 4) -> list:
+    """Discarding list that spares the first n_sink saved tokens: without overflow everything is kept; on
+    overflow (hist + new > window) the history may keep floor(window*(1-ratio)) - new tokens (not below 0,
+    not above hist): the first min(n_sink, budget) and the most recent rest.  Returns, per conversation,
+    the kept indices in increasing order."""
+    out = []
+    for h, n in zip(np.asarray(hist_len, dtype=np.int64), np.asarray(new_len, dtype=np.int64)):
+        if h + n <= window:
+            out.append(np.arange(h))
+            continue
+        budget = int(min(h, max(0, int(np.floor(window * (1.0 - ratio))) - n)))
+        sinks = min(int(n_sink), budget)
+        idx = set(range(sinks)) | set(range(int(h) - (budget - sinks), int(h)))
+        out.append(np.array(sorted(idx), dtype=np.int64))
+    return out
+
+
 def truncate_plan(hist_len, new_len, window: int, ratio: float = 0.5, policy: int = 0) -> np.ndarray:
     h, hp = _i(hist_len); n, np_ = _i(new_len)
     out = np.empty(h.shape[0], dtype=np.int32)

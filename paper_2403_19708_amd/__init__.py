@@ -11,4 +11,5 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     truncate_plan,
+    truncate_plan_sinks,
 )

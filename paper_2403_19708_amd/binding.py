@@ -21,7 +21,7 @@ STATUS = {0: "CA_OK", 1: "CA_ERR_INVALID_ARG", 2: "CA_ERR_OUT_OF_RANGE", 3: "CA_
 
 # every symbol include/ca.h declares
 SYMBOLS = ["ca_config_default", "ca_config_validate", "ca_batch_validate", "ca_create", "ca_destroy",
-           "ca_last_error", "ca_status_string", "ca_truncate_plan", "ca_rope_rebase", "ca_rebase_read",
+           "ca_last_error", "ca_status_string", "ca_truncate_plan", "ca_truncate_plan_sinks", "ca_rope_rebase", "ca_rebase_read",
            "ca_kv_load_layer", "ca_kv_append_layer", "ca_cached_prefill_attn", "ca_kv_save_layer",
            "ca_sync", "ca_join", "ca_profile_enable", "ca_profile_read"]
 
@@ -48,7 +48,8 @@ class _CBatch(C.Structure):
     _fields_ = [("n_seqs", C.c_int32), ("hist_len", C.POINTER(C.c_int32)),
                 ("keep_start", C.POINTER(C.c_int32)), ("new_len", C.POINTER(C.c_int32)),
                 ("block_table", C.POINTER(C.c_int32)), ("max_pages", C.c_int32),
-                ("num_pages", C.c_int32)]
+                ("num_pages", C.c_int32), ("keep_ranges", C.POINTER(C.c_int32)),
+                ("keep_range_count", C.POINTER(C.c_int32))]
 
 
 def lib_path() -> str:
@@ -81,6 +82,8 @@ def load_library():
     lib.ca_status_string.restype = C.c_char_p
     lib.ca_truncate_plan.argtypes = [i32p, i32p, C.c_int32, C.c_double, C.c_int32, C.c_int32, i32p]
     lib.ca_truncate_plan.restype = C.c_int
+    lib.ca_truncate_plan_sinks.argtypes = [i32p, i32p, C.c_int32, C.c_double, C.c_int32, C.c_int32, i32p, i32p]
+    lib.ca_truncate_plan_sinks.restype = C.c_int
     lib.ca_rope_rebase.argtypes = [vp, C.POINTER(_CBatch), vp]
     lib.ca_rope_rebase.restype = C.c_int
     lib.ca_rebase_read.argtypes = [vp, C.c_int32, i32p, C.c_int64, i64p]
@@ -155,15 +158,23 @@ def _i32(a):
     return a, a.ctypes.data_as(C.POINTER(C.c_int32))
 
 
-def _make_batch(hist_len, keep_start, new_len, block_table, num_pages):
+def _make_batch(hist_len, keep_start, new_len, block_table, num_pages, keep_ranges=None):
+    """keep_ranges: None, or one list of (begin, end) pairs per conversation (then keep_start may be None)."""
     h, hp = _i32(hist_len)
-    s, sp = _i32(keep_start)
+    s, sp = _i32(keep_start) if keep_start is not None else (None, None)
     n, np_ = _i32(new_len)
     bt, btp = _i32(block_table)
     if bt.ndim != 2:
         raise ValueError("block_table must be [n_seqs][max_pages]")
-    b = _CBatch(h.shape[0], hp, sp, np_, btp, bt.shape[1], int(num_pages))
-    return b, (h, s, n, bt)
+    rng = cnt = rp = cp = None
+    if keep_ranges is not None:
+        if len(keep_ranges) != h.shape[0]:
+            raise ValueError("keep_ranges needs one list of (begin, end) pairs per conversation")
+        cnt, cp = _i32([len(r) for r in keep_ranges])
+        flat = [pair for r in keep_ranges for pair in r]
+        rng, rp = _i32(np.asarray(flat, dtype=np.int32).reshape(-1, 2) if flat else np.zeros((1, 2), np.int32))
+    b = _CBatch(h.shape[0], hp, sp, np_, btp, bt.shape[1], int(num_pages), rp, cp)
+    return b, (h, s, n, bt, rng, cnt)
 
 
 def config_validate(cfg: Config) -> None:
@@ -175,11 +186,11 @@ def config_validate(cfg: Config) -> None:
         raise CaError(st, buf.value.decode())
 
 
-def batch_validate(cfg: Config, hist_len, keep_start, new_len, block_table, num_pages) -> None:
+def batch_validate(cfg: Config, hist_len, keep_start, new_len, block_table, num_pages, keep_ranges=None) -> None:
     lib = load_library()
     buf = C.create_string_buffer(512)
     c = cfg.to_c()
-    b, keep = _make_batch(hist_len, keep_start, new_len, block_table, num_pages)
+    b, keep = _make_batch(hist_len, keep_start, new_len, block_table, num_pages, keep_ranges)
     st = lib.ca_batch_validate(C.byref(c), C.byref(b), buf, 512)
     del keep
     if st != 0:
@@ -198,6 +209,22 @@ def truncate_plan(hist_len, new_len, window: int, ratio: float = 0.5, policy: in
     if st != 0:
         raise CaError(st, "ca_truncate_plan rejected its arguments")
     return out
+
+
+def truncate_plan_sinks(hist_len, new_len, window: int, ratio: float = 0.5, n_sink: int = 4) -> list:
+    """One list of (begin, end) kept ranges per conversation (the shape ca_batch.keep_ranges takes)."""
+    lib = load_library()
+    h, hp = _i32(hist_len)
+    n, np_ = _i32(new_len)
+    if h.shape != n.shape or h.ndim != 1:
+        raise ValueError("hist_len and new_len must be 1-D and equally long")
+    rng = np.zeros((h.shape[0], 2, 2), dtype=np.int32)
+    cnt = np.zeros(h.shape[0], dtype=np.int32)
+    st = lib.ca_truncate_plan_sinks(hp, np_, int(window), float(ratio), int(n_sink), h.shape[0],
+                                    rng.ctypes.data_as(C.POINTER(C.c_int32)), cnt.ctypes.data_as(C.POINTER(C.c_int32)))
+    if st != 0:
+        raise CaError(st, "ca_truncate_plan_sinks rejected its arguments")
+    return [[(int(rng[c, r, 0]), int(rng[c, r, 1])) for r in range(int(cnt[c]))] for c in range(h.shape[0])]
 
 
 class Context:
@@ -238,8 +265,8 @@ class Context:
             raise CaError(st, self._lib.ca_last_error(self._h).decode())
 
     # ---- Section 3.4 ------------------------------------------------------------------------
-    def rope_rebase(self, hist_len, keep_start, new_len, block_table, num_pages: int, stream=None):
-        b, keep = _make_batch(hist_len, keep_start, new_len, block_table, num_pages)
+    def rope_rebase(self, hist_len, keep_start, new_len, block_table, num_pages: int, stream=None, keep_ranges=None):
+        b, keep = _make_batch(hist_len, keep_start, new_len, block_table, num_pages, keep_ranges)
         st = self._lib.ca_rope_rebase(self._h, C.byref(b), _stream(stream))
         del keep
         self._check(st)

@@ -44,7 +44,10 @@ struct ca_ctx {
     bool has_plan = false;
     int32_t n_seqs = 0, max_pages = 0, num_pages = 0, n_items = 0, n_combine = 0, tile_rows = 128;
     int64_t total_q = 0, total_k = 0, total_n = 0;
-    std::vector<int32_t> hist_len, keep_start, new_len, n_keep, cu_q, cu_k;
+    std::vector<int32_t> hist_len, new_len, n_keep, cu_q, cu_k;
+    // kept saved tokens of conversation i: ranges keep_rng[keep_rng_at[i] .. keep_rng_at[i+1]) of (begin, end)
+    std::vector<int32_t> keep_rng_at;
+    std::vector<std::pair<int32_t, int32_t>> keep_rng;
     std::vector<int64_t> cu_n;
     std::vector<hipEvent_t> ev_ready;  // per layer
     std::vector<uint8_t> loaded;
@@ -258,8 +261,16 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
 ca_status ca_batch_validate(const ca_config *c, const ca_batch *b, char *err, int32_t err_len) {
     ca_status st = ca_config_validate(c, err, err_len);
     if (st != CA_OK) return st;
-    if (!b || !b->hist_len || !b->keep_start || !b->new_len || !b->block_table) {
+    if (!b || !b->hist_len || !b->new_len || !b->block_table) {
         set_err(err, err_len, "batch or one of its arrays is NULL");
+        return CA_ERR_INVALID_ARG;
+    }
+    if ((b->keep_ranges == nullptr) != (b->keep_range_count == nullptr)) {
+        set_err(err, err_len, "keep_ranges and keep_range_count must both be given or both NULL");
+        return CA_ERR_INVALID_ARG;
+    }
+    if (!b->keep_ranges && !b->keep_start) {
+        set_err(err, err_len, "neither keep_start nor keep_ranges is given");
         return CA_ERR_INVALID_ARG;
     }
     if (b->n_seqs < 1 || b->n_seqs > c->max_seqs) {
@@ -274,19 +285,42 @@ ca_status ca_batch_validate(const ca_config *c, const ca_batch *b, char *err, in
         set_err(err, err_len, "num_pages %d: slot index would overflow int32", b->num_pages);
         return CA_ERR_OUT_OF_RANGE;
     }
-    int64_t tot_k = 0, tot_q = 0;
+    int64_t tot_k = 0, tot_q = 0, range_at = 0;
     std::vector<uint8_t> seen((size_t)b->num_pages, 0);
     for (int32_t i = 0; i < b->n_seqs; ++i) {
-        const int64_t h = b->hist_len[i], s = b->keep_start[i], n = b->new_len[i];
+        const int64_t h = b->hist_len[i], n = b->new_len[i];
         if (h < 0 || n < 1) {
             set_err(err, err_len, "conversation %d: hist_len %lld < 0 or new_len %lld < 1", i, (long long)h, (long long)n);
             return CA_ERR_INVALID_ARG;
         }
-        if (s < 0 || s > h) {
-            set_err(err, err_len, "conversation %d: keep_start %lld outside [0, hist_len=%lld]", i, (long long)s, (long long)h);
-            return CA_ERR_OUT_OF_RANGE;
+        int64_t kept = 0;
+        if (b->keep_ranges) {
+            const int64_t cnt = b->keep_range_count[i];
+            if (cnt < 0 || cnt > h) {
+                set_err(err, err_len, "conversation %d: keep_range_count %lld outside [0, hist_len=%lld]", i, (long long)cnt, (long long)h);
+                return CA_ERR_OUT_OF_RANGE;
+            }
+            int64_t prev_end = 0;
+            for (int64_t r = 0; r < cnt; ++r) {
+                const int64_t rb = b->keep_ranges[2 * (range_at + r)], re = b->keep_ranges[2 * (range_at + r) + 1];
+                if (rb < prev_end || re <= rb || re > h) {
+                    set_err(err, err_len, "conversation %d: kept range %lld = [%lld, %lld) is empty, out of order or outside [0, hist_len=%lld]",
+                            i, (long long)r, (long long)rb, (long long)re, (long long)h);
+                    return CA_ERR_OUT_OF_RANGE;
+                }
+                kept += re - rb;
+                prev_end = re;
+            }
+            range_at += cnt;
+        } else {
+            const int64_t s = b->keep_start[i];
+            if (s < 0 || s > h) {
+                set_err(err, err_len, "conversation %d: keep_start %lld outside [0, hist_len=%lld]", i, (long long)s, (long long)h);
+                return CA_ERR_OUT_OF_RANGE;
+            }
+            kept = h - s;
         }
-        const int64_t ctx_len = h - s + n;
+        const int64_t ctx_len = kept + n;
         if (ctx_len > c->max_positions) {
             set_err(err, err_len, "conversation %d: context %lld exceeds max_positions %d (truncate first)", i,
                     (long long)ctx_len, c->max_positions);
@@ -316,6 +350,36 @@ ca_status ca_batch_validate(const ca_config *c, const ca_batch *b, char *err, in
         set_err(err, err_len, "batch has %lld context / %lld new tokens, limits are %lld / %lld", (long long)tot_k,
                 (long long)tot_q, (long long)c->max_batch_kv_tokens, (long long)c->max_batch_q_tokens);
         return CA_ERR_OUT_OF_RANGE;
+    }
+    return CA_OK;
+}
+
+ca_status ca_truncate_plan_sinks(const int32_t *hist_len, const int32_t *new_len, int32_t window, double ratio,
+                                 int32_t n_sink, int32_t n, int32_t *ranges_out, int32_t *count_out) {
+    if (!hist_len || !new_len || !ranges_out || !count_out || n < 0 || n_sink < 0) return CA_ERR_INVALID_ARG;
+    if (window < 1 || !(ratio > 0.0) || !(ratio < 1.0)) return CA_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (hist_len[i] < 0 || new_len[i] < 0) return CA_ERR_INVALID_ARG;
+    const int64_t keep_target = (int64_t)std::floor((double)window * (1.0 - ratio));
+    for (int32_t i = 0; i < n; ++i) {
+        const int64_t h = hist_len[i], fresh = new_len[i];
+        int32_t *r = ranges_out + 4 * (int64_t)i;
+        r[0] = r[1] = r[2] = r[3] = 0;
+        int32_t cnt = 0;
+        if (h + fresh <= window) {
+            if (h > 0) { r[0] = 0; r[1] = (int32_t)h; cnt = 1; }
+        } else {
+            const int64_t budget = std::min<int64_t>(h, std::max<int64_t>(0, keep_target - fresh));
+            const int64_t sinks = std::min<int64_t>(n_sink, budget);
+            const int64_t recent = budget - sinks;                 // tokens [h - recent, h)
+            if (sinks > 0 && recent > 0 && h - recent <= sinks) {  // the two pieces touch or overlap
+                r[0] = 0; r[1] = (int32_t)h; cnt = 1;              // (only when everything is kept)
+            } else {
+                if (sinks > 0) { r[2 * cnt] = 0; r[2 * cnt + 1] = (int32_t)sinks; ++cnt; }
+                if (recent > 0) { r[2 * cnt] = (int32_t)(h - recent); r[2 * cnt + 1] = (int32_t)h; ++cnt; }
+            }
+        }
+        count_out[i] = cnt;
     }
     return CA_OK;
 }
@@ -530,14 +594,26 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
     }
 
     ctx->hist_len.assign(b->hist_len, b->hist_len + B);
-    ctx->keep_start.assign(b->keep_start, b->keep_start + B);
+    ctx->keep_rng_at.assign(B + 1, 0);
+    ctx->keep_rng.clear();
+    for (int i = 0, at = 0; i < B; ++i) {
+        if (b->keep_ranges) {
+            for (int r = 0; r < b->keep_range_count[i]; ++r, ++at)
+                ctx->keep_rng.push_back({b->keep_ranges[2 * at], b->keep_ranges[2 * at + 1]});
+        } else if (b->keep_start[i] < b->hist_len[i]) {
+            ctx->keep_rng.push_back({b->keep_start[i], b->hist_len[i]});
+        }
+        ctx->keep_rng_at[i + 1] = (int32_t)ctx->keep_rng.size();
+    }
     ctx->new_len.assign(b->new_len, b->new_len + B);
     ctx->n_keep.resize(B);
     ctx->cu_q.assign(B + 1, 0);
     ctx->cu_k.assign(B + 1, 0);
     ctx->cu_n.assign(B + 1, 0);
     for (int i = 0; i < B; ++i) {
-        ctx->n_keep[i] = b->hist_len[i] - b->keep_start[i];
+        int32_t kept = 0;
+        for (int r = ctx->keep_rng_at[i]; r < ctx->keep_rng_at[i + 1]; ++r) kept += ctx->keep_rng[r].second - ctx->keep_rng[r].first;
+        ctx->n_keep[i] = kept;
         ctx->cu_q[i + 1] = ctx->cu_q[i] + b->new_len[i];
         ctx->cu_k[i + 1] = ctx->cu_k[i] + ctx->n_keep[i] + b->new_len[i];
         ctx->cu_n[i + 1] = ctx->cu_n[i] + ctx->n_keep[i];
@@ -866,9 +942,15 @@ ca_status ca_kv_load_layer(ca_ctx *ctx, int32_t layer, const void *const *src_k,
         for (int i = 0; i < B; ++i) {
             const int64_t n = ctx->n_keep[i];
             if (n == 0) continue;
-            const size_t bytes = (size_t)n * rb, src_off = (size_t)ctx->keep_start[i] * rb, dst_off = (size_t)ctx->cu_n[i] * rb;
-            CA_HIP(ctx, hipMemcpyAsync(sk + dst_off, (const uint8_t *)src_k[i] + src_off, bytes, hipMemcpyDefault, ctx->s_copy));
-            CA_HIP(ctx, hipMemcpyAsync(sv + dst_off, (const uint8_t *)src_v[i] + src_off, bytes, hipMemcpyDefault, ctx->s_copy));
+            // the kept ranges land back to back in the slot: truncation and discarding are source offsets
+            size_t dst_off = (size_t)ctx->cu_n[i] * rb;
+            for (int r = ctx->keep_rng_at[i]; r < ctx->keep_rng_at[i + 1]; ++r) {
+                const size_t src_off = (size_t)ctx->keep_rng[r].first * rb;
+                const size_t bytes = (size_t)(ctx->keep_rng[r].second - ctx->keep_rng[r].first) * rb;
+                CA_HIP(ctx, hipMemcpyAsync(sk + dst_off, (const uint8_t *)src_k[i] + src_off, bytes, hipMemcpyDefault, ctx->s_copy));
+                CA_HIP(ctx, hipMemcpyAsync(sv + dst_off, (const uint8_t *)src_v[i] + src_off, bytes, hipMemcpyDefault, ctx->s_copy));
+                dst_off += bytes;
+            }
             segs.push_back({sk, sv, ctx->cu_n[i], 0, (int32_t)n, i});
         }
         CA_HIP(ctx, prof_end(ctx, iv_copy, ctx->s_copy));
@@ -886,7 +968,12 @@ ca_status ca_kv_load_layer(ca_ctx *ctx, int32_t layer, const void *const *src_k,
         for (int i = 0; i < B; ++i) {
             const int64_t n = ctx->n_keep[i];
             if (n == 0) continue;
-            segs.push_back({(uint8_t *)src_k[i], (uint8_t *)src_v[i], ctx->keep_start[i], 0, (int32_t)n, i});
+            int32_t at = 0;      // context token the range starts at
+            for (int r = ctx->keep_rng_at[i]; r < ctx->keep_rng_at[i + 1]; ++r) {
+                const int32_t len = ctx->keep_rng[r].second - ctx->keep_rng[r].first;
+                segs.push_back({(uint8_t *)src_k[i], (uint8_t *)src_v[i], ctx->keep_rng[r].first, at, len, i});
+                at += len;
+            }
         }
         int iv_unpack;
         CA_HIP(ctx, prof_begin(ctx, kProfUnpack, ctx->s_unpack, &iv_unpack));

@@ -134,3 +134,38 @@ def test_create_without_gpu_fails_cleanly(lib):
     with pytest.raises(ca.CaError) as e:
         ca.Context(ca.Config())
     assert e.value.status_name in ("CA_ERR_HIP", "CA_ERR_OUT_OF_RANGE")
+
+
+def _ranges_to_indices(ranges):
+    return np.concatenate([np.arange(b, e) for b, e in ranges]) if ranges else np.zeros(0, np.int64)
+
+
+def test_sink_planner_agrees_with_oracle(lib):
+    rng = np.random.default_rng(7)
+    for W, r, sink in ((4096, 0.5, 4), (4096, 0.5, 0), (512, 0.25, 16), (97, 0.3, 200), (64, 0.75, 1)):
+        h = rng.integers(0, 3 * W, 300).astype(np.int32)
+        n = rng.integers(0, W, 300).astype(np.int32)
+        got = ca.truncate_plan_sinks(h, n, W, r, sink)
+        want = oracle.kept_indices_sinks(h, n, W, r, sink)
+        for c in range(300):
+            assert len(got[c]) <= 2
+            assert np.array_equal(_ranges_to_indices(got[c]), want[c]), (W, r, sink, c)
+            assert all(b < e for b, e in got[c]) and (len(got[c]) < 2 or got[c][0][1] < got[c][1][0])
+
+
+def test_batch_validation_of_kept_ranges(lib):
+    h, k, n, bt, p = _good_batch()                  # hist 40, 0, 100; new 5, 17, 3
+    cfg = ca.Config(max_positions=128)
+    ca.batch_validate(cfg, h, None, n, bt, p, keep_ranges=[[(0, 4), (20, 40)], [], [(3, 9), (9, 10), (50, 55)]])
+    for bad, status in (
+            ([[(0, 4), (3, 40)], [], []], "CA_ERR_OUT_OF_RANGE"),          # overlap
+            ([[(10, 4)], [], []], "CA_ERR_OUT_OF_RANGE"),                  # empty / reversed
+            ([[(0, 41)], [], []], "CA_ERR_OUT_OF_RANGE"),                  # beyond hist_len
+            ([[(20, 40), (0, 4)], [], []], "CA_ERR_OUT_OF_RANGE"),         # not increasing
+            ([[], [(0, 1)], []], "CA_ERR_OUT_OF_RANGE"),                   # hist_len 0 has nothing to keep
+            ([[(0, 40)], [], [(0, 100)]], "CA_ERR_OUT_OF_RANGE")):         # 100 + 3 tokens need 7 pages, table has 4
+        with pytest.raises(ca.CaError) as e:
+            ca.batch_validate(cfg, h, None, n, bt, p, keep_ranges=bad)
+        assert e.value.status_name == status, bad
+    with pytest.raises(ca.CaError):
+        ca.batch_validate(cfg, h, None, n, bt, p)                           # neither keep_start nor ranges

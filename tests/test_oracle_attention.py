@@ -205,3 +205,49 @@ def test_rejects_bad_arguments():
         oracle.cached_attention(K[:4], V[:4], Q[4:], K[4:], V[4:], keep_start=5)
     with pytest.raises(ValueError):
         oracle.cached_attention(K[:4], V[:4], Q[4:], K[4:], V[4:], keep_start=-1)
+
+
+# ---- token discarding lists (Section 3.4, last paragraph) ------------------------------------------------
+
+@pytest.mark.parametrize("kept_kind", ["suffix", "sinks+recent", "scattered", "nothing"])
+def test_pruned_history_equals_recompute_over_the_kept_tokens(kept_kind):
+    """A discarding list leaves an arbitrary subsequence of the saved tokens; reuse over it must equal
+    what a recomputing engine produces on the token sequence [kept history | new turn] at dense
+    positions -- and, for a kept suffix, the keep_start path."""
+    Lh, Ln, Hq, Hkv, D = 90, 14, 4, 2, 64
+    Q, K, V = make_case(Lh, Ln, Hq, Hkv, D, seed=5)
+    kept = {"suffix": np.arange(37, Lh), "sinks+recent": np.r_[0:4, 60:Lh],
+            "scattered": np.array(sorted(np.random.default_rng(3).choice(Lh, 41, replace=False))),
+            "nothing": np.zeros(0, np.int64)}[kept_kind]
+    got = oracle.cached_attention_kept(K[:Lh], V[:Lh], kept, Q[Lh:], K[Lh:], V[Lh:])
+    seq = np.r_[kept, np.arange(Lh, Lh + Ln)]
+    # queries of the history rows do not matter for the new rows; take any (here: the saved ones)
+    want = full_recompute(Q[seq], K[seq], V[seq])[len(kept):]
+    assert np.abs(got - want).max() < 1e-12
+    if kept_kind == "suffix":
+        same = oracle.cached_attention(K[:Lh], V[:Lh], Q[Lh:], K[Lh:], V[Lh:], keep_start=37)
+        assert np.array_equal(got, same)
+    if kept_kind == "scattered":      # dropping different tokens must change the result
+        other = oracle.cached_attention_kept(K[:Lh], V[:Lh], np.arange(Lh - 41, Lh), Q[Lh:], K[Lh:], V[Lh:])
+        assert np.abs(got - other).max() > 1e-3
+
+
+def test_sink_discarding_list_closed_forms():
+    """Budget arithmetic of the sink-sparing list against hand-computed cases (window 4096, ratio 0.5:
+    2048 tokens of [history | new] survive an overflow, as in Section 4.1's 4K/2K setting)."""
+    W = 4096
+    k = oracle.kept_indices_sinks([3000, 4000, 4000, 5000, 10, 4090, 0], [1000, 100, 2048, 3000, 4000, 7, 50], W, 0.5, 4)
+    assert np.array_equal(k[0], np.arange(3000))                                  # 4000 <= 4096: no overflow
+    assert np.array_equal(k[1], np.r_[0:4, 4000 - 1944:4000]) and len(k[1]) == 1948   # 2048 - 100 kept
+    assert len(k[2]) == 0 and len(k[3]) == 0                                      # the new turn fills the budget
+    assert np.array_equal(k[4], np.arange(10))                                    # 4010 <= 4096
+    assert np.array_equal(k[5], np.r_[0:4, 4090 - 2037:4090])                     # 2041 kept
+    assert len(k[6]) == 0
+    # more sinks than budget: only sinks; zero sinks: the plain keep-recent rule of policy 0
+    k = oracle.kept_indices_sinks([4000], [2040], W, 0.5, 64)
+    assert np.array_equal(k[0], np.arange(8))
+    h, n = np.array([4000, 6000, 100]), np.array([500, 100, 30])
+    k0 = oracle.kept_indices_sinks(h, n, W, 0.5, 0)
+    s0 = oracle.truncate_plan(h, n, W, 0.5, 0)
+    for c in range(3):
+        assert np.array_equal(k0[c], np.arange(s0[c], h[c]))
