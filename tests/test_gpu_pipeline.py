@@ -65,6 +65,41 @@ def test_pipeline_orderings_give_identical_bits():
             at += int(case.new_len[c])
 
 
+def test_next_job_preloads_while_the_current_job_computes():
+    """Section 3.2.1's read buffer across jobs: the first layers of job 2 are loaded (its own context,
+    its own staging slots and streams) while job 1 is still in its layers.  Both jobs must produce the
+    bits they produce when run alone, one after the other."""
+    job1 = Case([400, 90], [70, 200], [0, 30], 4, 2, 128, seed=57, n_layers=4, window=1024)
+    job2 = Case([150, 600, 20], [33, 5, 140], [10, 0, 0], 4, 2, 128, seed=58, n_layers=4, window=1024)
+    alone = [run_stack(job, "pinned", depth=2, mode=0, sync_every_op=True) for job in (job1, job2)]
+    a, b = GpuRun(job1, tier="pinned", pipeline_depth=2), GpuRun(job2, tier="pinned", pipeline_depth=2)
+    try:
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        a.rebase(s1)
+        for l in range(job1.n_layers):
+            a.load(l)
+        b.rebase(s2)
+        for l in range(2):                       # job 2's read buffer fills before job 1 has computed anything
+            b.load(l)
+        for l in range(job1.n_layers):
+            a.append(l, s1); a.attn(l, s1); a.save(l, after_stream=s1)
+            if l == 1:
+                for l2 in range(2, job2.n_layers):
+                    b.load(l2)
+        for l in range(job2.n_layers):
+            b.append(l, s2); b.attn(l, s2); b.save(l, after_stream=s2)
+        a.ctx.join(s1); b.ctx.join(s2)
+        a.finish(); b.finish()
+        for run, (ref_out, ref_tier), job in ((a, alone[0], job1), (b, alone[1], job2)):
+            for l in range(job.n_layers):
+                assert np.array_equal(torch_to_bits(run.out[l]), ref_out[l]), l
+                got = [torch_to_bits(t) for t in run.host_k[l]] + [torch_to_bits(t) for t in run.host_v[l]]
+                for x, y in zip(got, ref_tier[l]):
+                    assert np.array_equal(x, y), l
+    finally:
+        a.close(); b.close()
+
+
 @pytest.mark.parametrize("variant", [3, 2], ids=["staged", "direct"])
 def test_both_tile_sizes_agree_with_oracle(variant):
     case = Case([500, 90], [200, 31], [37, 0], 8, 2, 128, seed=52)
