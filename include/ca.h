@@ -118,7 +118,8 @@ typedef struct {
 
 /* ---- context ------------------------------------------------------------------------ */
 
-/* Fills *cfg with defaults (page 16, base 10000, half-split pairs, depth 2, MFMA kernel). */
+/* Fills *cfg with defaults (page 16, base 10000, half-split pairs, depth 2, attention kernel
+ * chosen by the window, key splitting on).                                                  */
 void ca_config_default(ca_config *cfg);
 
 /* Host-only checks of a configuration / a batch against a configuration.  Used by every

@@ -11,7 +11,14 @@
 //     is spent on staging.  The only vector-memory instructions inside the walk are these loads,
 //     so s_waitcnt vmcnt(N) with a constant N releases exactly the tile that is needed next.
 //   * The page ids of the conversation are copied into LDS once; the dependent chain
-//     block table -> page -> row costs an LDS read.
+//     block table -> page -> row costs an LDS read.  On interior tiles a load's page and base address
+//     are wave-uniform: all page ids of an iteration are read before the first is used (one LDS round
+//     trip), and the scalar address arithmetic and the loads are issued after the first matrix
+//     instructions of the tile, where they cost nothing.
+//   * An item may own only a share [key_begin, key_end) of the keys its rows see (the host splits long
+//     row tiles over several workgroups when a batch would otherwise leave compute units idle).  Such an
+//     item leaves unnormalised sums, reference maxima and denominators in a scratch buffer and
+//     combine_kernel merges the shares of a row tile.
 //   * Since the LDS side of such a load is fixed (lane l -> byte l*16 of a 1 KiB chunk), the layout
 //     is chosen on the global side: a chunk holds KPC = 1024/(2D) keys, piece-major
 //     (slot = piece*KPC + key_in_chunk), chunks padded by KPC*16 bytes.  With it the A-operand reads
