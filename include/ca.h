@@ -226,7 +226,10 @@ ca_status ca_join(ca_ctx *ctx, void *stream);
  * ca_profile_read synchronises the device, returns the summed milliseconds and the number of
  * intervals of one kind recorded since the last read of that kind, and forgets them.
  * kind: 0 load copy-in (one interval per layer), 1 unpack kernel(s), 2 append kernel(s),
- *       3 attention kernel, 4 pack kernel(s), 5 save copy-out (one interval per layer).        */
+ *       3 attention kernel, 4 pack kernel(s), 5 save copy-out (one interval per layer).
+ * on: 0 off; 1 every kind; any other value 2 * mask times only the kinds k with bit k of mask
+ *     set (events cost a few per cent of a step of short kernels; a caller that needs one
+ *     kernel's duration inside a timed region can restrict them to that kind).                 */
 ca_status ca_profile_enable(ca_ctx *ctx, int32_t on);
 ca_status ca_profile_read(ca_ctx *ctx, int32_t kind, double *total_ms, int64_t *count);
 

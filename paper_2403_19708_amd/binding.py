@@ -335,8 +335,15 @@ class Context:
 
     PROFILE_KINDS = {"copy_in": 0, "unpack": 1, "append": 2, "attn": 3, "pack": 4, "copy_out": 5}
 
-    def profile_enable(self, on: bool = True):
-        self._check(self._lib.ca_profile_enable(self._h, 1 if on else 0))
+    def profile_enable(self, on: bool = True, kinds=None):
+        """kinds: None = every kind, else an iterable of kind names/numbers to time"""
+        arg = 1 if on else 0
+        if on and kinds is not None:
+            mask = 0
+            for k in kinds:
+                mask |= 1 << (self.PROFILE_KINDS[k] if isinstance(k, str) else int(k))
+            arg = 2 * mask
+        self._check(self._lib.ca_profile_enable(self._h, arg))
 
     def profile_read(self, kind) -> tuple[float, int]:
         """(summed milliseconds, number of intervals) of one kind since the last read."""

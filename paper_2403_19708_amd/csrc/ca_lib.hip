@@ -54,6 +54,7 @@ struct ca_ctx {
     // optional timing of the library's own GPU work (ca_profile_*)
     struct Interval { int32_t kind; hipEvent_t start, stop; };
     bool profiling = false;
+    uint32_t profile_mask = ~0u;       // bit k: intervals of kind k are recorded
     std::vector<Interval> intervals;
     std::vector<hipEvent_t> spare_events;
     std::string err;
@@ -102,7 +103,7 @@ hipError_t prof_event(ca_ctx *ctx, hipEvent_t *ev) {
 // Opens a timed interval on `stream`; returns its index or -1 when profiling is off.
 hipError_t prof_begin(ca_ctx *ctx, int kind, hipStream_t stream, int *idx) {
     *idx = -1;
-    if (!ctx->profiling) return hipSuccess;
+    if (!ctx->profiling || !(ctx->profile_mask & (1u << kind))) return hipSuccess;
     ca_ctx::Interval iv{kind, nullptr, nullptr};
     hipError_t e = prof_event(ctx, &iv.start);
     if (e != hipSuccess) return e;
@@ -1171,6 +1172,7 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
 ca_status ca_profile_enable(ca_ctx *ctx, int32_t on) {
     if (!ctx) return CA_ERR_INVALID_ARG;
     ctx->profiling = on != 0;
+    ctx->profile_mask = (on == 1 || on == 0) ? ~0u : ((uint32_t)on >> 1);
     return CA_OK;
 }
 
