@@ -190,6 +190,24 @@ def test_small_batch_splits_keys_over_workgroups(shape, split):
         run.close()
 
 
+@pytest.mark.parametrize("variant", [2, 3], ids=["direct", "staged"])
+def test_context_fills_the_largest_window_of_the_direct_kernel(variant):
+    """One conversation whose context is exactly 32768 tokens: every entry of the LDS-direct kernel's page
+    table is in use, the last tile ends on the window, positions reach 32767 (and the few row tiles of a
+    single conversation are split over many workgroups)."""
+    W, new = 32768, 200
+    case = Case([W - new], [new], [0], 2, 1, 128, seed=29, window=W)
+    run = GpuRun(case, tier="device", attn_variant=variant)
+    try:
+        run.rebase()
+        run.run_layer(0)
+        run.finish()
+        check_contract(run.out_f64(0, 0), case.oracle_out(0, 0), variant)
+        check_tight(run.out_f64(0, 0), case.oracle_out(0, 0), W - new, variant)
+    finally:
+        run.close()
+
+
 @pytest.mark.parametrize("window", [4096, 65536], ids=["direct-by-default", "staged-beyond-32768"])
 def test_default_variant_follows_the_window(window):
     """attn_variant 0 takes the LDS-direct kernel while its page-id table holds the window and the
