@@ -90,6 +90,13 @@ typedef struct {
     int32_t attn_split;      /* 0: when a batch has too few row tiles to keep all compute units */
                              /* busy, the LDS-direct kernel splits the keys of long tiles over  */
                              /* several workgroups and merges their shares; 1: never split      */
+    int32_t attn_prerotate;  /* the LDS-direct kernel applies the rotary encoding to a key in    */
+                             /* every row tile that reads it; when many row tiles share the keys */
+                             /* of a (conversation, kv head) (long new turns, grouped heads) it  */
+                             /* is cheaper to rotate the batch's keys once per layer into a      */
+                             /* scratch copy first.  0: decide per batch (three or more 256-row  */
+                             /* tiles per (conversation, kv head) on average); 1: never;         */
+                             /* 2: always (256-row tiles are then used whatever the batch)       */
     int32_t require_load;    /* 1: attention on a layer with kept history that was not loaded */
                              /* under the current plan fails with CA_ERR_NOT_READY            */
     int32_t device;          /* HIP device ordinal                                            */

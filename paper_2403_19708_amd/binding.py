@@ -40,7 +40,7 @@ class _CConfig(C.Structure):
                 ("max_seqs", C.c_int32), ("max_batch_kv_tokens", C.c_int64),
                 ("max_batch_q_tokens", C.c_int64), ("load_mode", C.c_int32), ("save_mode", C.c_int32),
                 ("attn_variant", C.c_int32), ("attn_tile_rows", C.c_int32), ("attn_split", C.c_int32),
-                ("require_load", C.c_int32),
+                ("attn_prerotate", C.c_int32), ("require_load", C.c_int32),
                 ("device", C.c_int32)]
 
 
@@ -127,6 +127,7 @@ class Config:
     attn_variant: int = 0
     attn_tile_rows: int = 0
     attn_split: int = 0
+    attn_prerotate: int = 0
     require_load: int = 1
     device: int = 0
 

@@ -127,7 +127,10 @@ __device__ inline void rotate_dword(uint32_t &pa, uint32_t &pb, const float2 (&c
 // NW = 8, BN = 64 (one workgroup per compute unit, 256-row tiles) and NW = 4, BN = 32 (two independent
 // workgroups per compute unit, 128-row tiles: the two wavefronts that share a SIMD then belong to
 // different workgroups, are not in lock step, and one's matrix products run under the other's softmax).
-template <int D, int STYLE, int NW, int BN>
+// ROT = false: the keys come already rotated from a scratch copy of the context (rotate_keys_kernel below),
+// dense pages numbered per conversation; used when many row tiles share the keys of a (conversation, kv head)
+// and rotating them once beats rotating them in every tile.
+template <int D, int STYLE, int NW, int BN, bool ROT = true>
 __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     constexpr int NTHREADS = 64 * NW;
     constexpr int MB = BN / 32;              // 32-key blocks of S^T per tile
@@ -208,16 +211,18 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     }
 
     // ---- rotary pass: this thread's (key, piece pair) of every K tile ------------------------------
-    const bool rot_active = ROT_TASKS >= NTHREADS || tid < ROT_TASKS;
+    const bool rot_active = ROT && (ROT_TASKS >= NTHREADS || tid < ROT_TASKS);
     const int rot_kk = tid / (PPR / 2);
     const int rot_pr = tid % (PPR / 2);
     const int rot_off = (rot_kk / KPC) * CH + (rot_pr * KPC + rot_kk % KPC) * 16;   // piece rot_pr; partner +512
     constexpr int ROT_PARTNER = (PPR / 2) * KPC * 16;
     float2 k_step[8], k_cs[8];
-    load_cs<D, STYLE>(a.rope, BN, rot_pr, k_step);
+    if (ROT) load_cs<D, STYLE>(a.rope, BN, rot_pr, k_step);
     // first position of this thread's key; a thread whose first key lies past the visible range never sees a
     // visible one later either, so clamping it is harmless (and keeps the read inside the table)
-    load_cs<D, STYLE>(a.rope, rot_active ? min(t_begin * BN + rot_kk, kmax - 1) : 0, rot_pr, k_cs);
+    if (ROT) load_cs<D, STYLE>(a.rope, rot_active ? min(t_begin * BN + rot_kk, kmax - 1) : 0, rot_pr, k_cs);
+    const uint16_t *const k_src = ROT ? a.k_pool : a.k_rot;
+    const int k_page0 = ROT ? 0 : a.dense_page0[c];          // ROT = false: key page i of the conversation is k_page0 + i
     uint4 kx, ky;
 
     // ---- operand addresses inside a stage ---------------------------------------------------------------
@@ -258,8 +263,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int t = min(kt0 + ld_tok[i], kmax - 1);
-            const int page = pg[t >> 4];
-            const uint16_t *base = ld_is_v[i] ? a.v_pool : a.k_pool;
+            const int page = (ROT || ld_is_v[i]) ? pg[t >> 4] : k_page0 + (t >> 4);
+            const uint16_t *base = ld_is_v[i] ? a.v_pool : k_src;
             const uint16_t *src = base + (((int64_t)page * Hkv + g) * kPageSize + (t & 15)) * D + ld_goff[i];
             dma16(src, __builtin_amdgcn_readfirstlane(lds_offset(stage + ld_loff[i])));
         }
@@ -274,7 +279,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
         const uint32_t stage = __builtin_amdgcn_readfirstlane(lds_offset(ring)) + (uint32_t)((tile % NS) * STAGE);
         int page_v[NI];                     // all page ids first: one LDS round trip instead of NI
 #pragma unroll
-        for (int i = 0; i < NI; ++i) page_v[i] = pg[(kt0 + ((wave_u + NW * i) % CHUNKS) * KPC) >> 4];
+        for (int i = 0; i < NI; ++i) {
+            const int pi = (kt0 + ((wave_u + NW * i) % CHUNKS) * KPC) >> 4;
+            page_v[i] = (ROT || wave_u + NW * i >= CHUNKS) ? pg[pi] : k_page0 + pi;
+        }
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int cid = wave_u + NW * i;
@@ -282,7 +290,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
             const int jch = cid % CHUNKS;
             const int t0 = kt0 + jch * KPC;                                 // first key of the chunk
             const int page = __builtin_amdgcn_readfirstlane(page_v[i]);
-            const uint16_t *base = (is_v ? a.v_pool : a.k_pool) + (((int64_t)page * Hkv + g) * kPageSize + (t0 & 15)) * D;
+            const uint16_t *base = (is_v ? a.v_pool : k_src) + (((int64_t)page * Hkv + g) * kPageSize + (t0 & 15)) * D;
             dma16_sbase(base, ld_lane_off, stage + (uint32_t)((is_v ? TILE : 0) + jch * CH));
         }
     };
@@ -539,6 +547,34 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a) {
     *reinterpret_cast<uint2 *>(a.out + ((int64_t)(a.cu_q[ci.seq] + j) * a.n_q_heads + head) * D + d) = ob;
 }
 
+// Rotates the keys of the whole batch context once (Section 3.4: the rebased positional encoding, applied
+// when the cache is used): dense page dp of the scratch copy = pool page rot_src_page[dp] with token slot s
+// rotated at position rot_pos0[dp] + s, in fp32 from the table, rounded to bf16 -- the same values the fused
+// path forms tile by tile (there with the rotation advanced by recurrence).  blockIdx = (dense page, kv head);
+// a thread owns one (token, pair of 16-byte pieces).  Slots past the end of a context hold whatever the pool
+// holds; nobody reads them.
+template <int D, int STYLE>
+__global__ __launch_bounds__(D) void rotate_keys_kernel(AttnArgs a) {
+    constexpr int HALF = D / 2;
+    constexpr int PAIRS = D / 16;                       // piece pairs per row
+    static_assert(kPageSize * PAIRS == D, "one thread per (token of the page, piece pair)");
+    const int dp = blockIdx.x, g = blockIdx.y;
+    const int key = threadIdx.x / PAIRS, pr = threadIdx.x % PAIRS;
+    if (key >= kPageSize) return;
+    const int pos = min(a.rot_pos0[dp] + key, a.max_positions - 1);
+    const int64_t src = (((int64_t)a.rot_src_page[dp] * a.n_kv_heads + g) * kPageSize + key) * D;
+    const int64_t dst = (((int64_t)dp * a.n_kv_heads + g) * kPageSize + key) * D;
+    uint4 x = *reinterpret_cast<const uint4 *>(a.k_pool + src + 8 * pr);
+    uint4 y = *reinterpret_cast<const uint4 *>(a.k_pool + src + HALF + 8 * pr);
+    float2 cs[8];
+    load_cs<D, STYLE>(a.rope, pos, pr, cs);
+    uint32_t *px = reinterpret_cast<uint32_t *>(&x), *py = reinterpret_cast<uint32_t *>(&y);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) rotate_dword<STYLE>(px[w], py[w], cs, w);
+    *reinterpret_cast<uint4 *>(a.k_rot + dst + 8 * pr) = x;
+    *reinterpret_cast<uint4 *>(a.k_rot + dst + HALF + 8 * pr) = y;
+}
+
 template <int NW, int BN>
 hipError_t launch_shape(const AttnArgs &a, hipStream_t stream) {
     dim3 grid(a.n_items), block(64 * NW);
@@ -561,7 +597,27 @@ hipError_t launch_attn_dma(const AttnArgs &a, hipStream_t stream) {
     if (a.n_items <= 0) return hipSuccess;
     if (a.n_combine > 0 && (a.partial == nullptr || a.combine == nullptr)) return hipErrorInvalidValue;
     hipError_t e;
-    if (a.tile_rows == 256) e = launch_shape<8, 64>(a, stream);
+    if (a.prerotate) {
+        if (a.tile_rows != 256 || !a.k_rot || !a.dense_page0 || !a.rot_src_page || !a.rot_pos0 || a.n_dense_pages <= 0)
+            return hipErrorInvalidValue;
+        const dim3 rgrid(a.n_dense_pages, a.n_kv_heads), grid(a.n_items), block(512);
+        if (a.head_dim == 128 && a.rope_style == 0) {
+            hipLaunchKernelGGL((rotate_keys_kernel<128, 0>), rgrid, dim3(128), 0, stream, a);
+            hipLaunchKernelGGL((attn_dma_kernel<128, 0, 8, 64, false>), grid, block, 0, stream, a);
+        } else if (a.head_dim == 128) {
+            hipLaunchKernelGGL((rotate_keys_kernel<128, 1>), rgrid, dim3(128), 0, stream, a);
+            hipLaunchKernelGGL((attn_dma_kernel<128, 1, 8, 64, false>), grid, block, 0, stream, a);
+        } else if (a.head_dim == 64 && a.rope_style == 0) {
+            hipLaunchKernelGGL((rotate_keys_kernel<64, 0>), rgrid, dim3(64), 0, stream, a);
+            hipLaunchKernelGGL((attn_dma_kernel<64, 0, 8, 64, false>), grid, block, 0, stream, a);
+        } else if (a.head_dim == 64) {
+            hipLaunchKernelGGL((rotate_keys_kernel<64, 1>), rgrid, dim3(64), 0, stream, a);
+            hipLaunchKernelGGL((attn_dma_kernel<64, 1, 8, 64, false>), grid, block, 0, stream, a);
+        } else {
+            return hipErrorInvalidValue;
+        }
+        e = hipGetLastError();
+    } else if (a.tile_rows == 256) e = launch_shape<8, 64>(a, stream);
     else if (a.tile_rows == 128) e = launch_shape<4, 32>(a, stream);
     else return hipErrorInvalidValue;
     if (e != hipSuccess || a.n_combine <= 0) return e;

@@ -90,6 +90,14 @@ struct AttnArgs {
     float *partial;          // shares of split row tiles: per part [tile_rows][head_dim] sums, [tile_rows] maxima,
                              // [tile_rows] denominators (fp32)
     const float2 *rope;      // [max_positions][head_dim/2] (cos, sin)
+    // keys rotated once per batch and layer instead of in every row tile (prerotate != 0):
+    uint16_t *k_rot;             // scratch copy of the keys, dense pages [n_dense_pages][n_kv_heads][16][head_dim]
+    const int32_t *dense_page0;  // [n_seqs] first dense page of a conversation
+    const int32_t *rot_src_page; // [n_dense_pages] pool page a dense page is rotated from
+    const int32_t *rot_pos0;     // [n_dense_pages] position of its first token
+    int32_t n_dense_pages;
+    int32_t prerotate;
+    int32_t max_positions;
     int32_t n_items;
     int32_t n_combine;
     int32_t total_q;

@@ -39,6 +39,11 @@ struct ca_ctx {
            off_q_seq = 0, off_slot_map = 0, upload_bytes = 0;
     size_t items_capacity = 0;         // work items the image has room for
     float *partial = nullptr;          // shares of row tiles whose keys were split over workgroups
+    uint16_t *k_rot = nullptr;         // keys of the batch context rotated once per layer (dense pages)
+    size_t k_rot_pages = 0;
+    size_t off_dense0 = 0, off_rot_src = 0, off_rot_pos = 0;
+    int32_t n_dense_pages = 0;
+    bool prerotate = false;
     int32_t n_cus = 256;               // compute units of the device (balancing target)
     // current plan (host copies)
     bool has_plan = false;
@@ -191,6 +196,7 @@ void ca_config_default(ca_config *c) {
     c->attn_variant = 0;
     c->attn_tile_rows = 0;
     c->attn_split = 0;
+    c->attn_prerotate = 0;
     c->require_load = 1;
     c->device = 0;
 }
@@ -254,6 +260,7 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
         set_err(err, err_len, "attn_tile_rows %d unsupported (0, 128 or 256)", c->attn_tile_rows);
         return CA_ERR_UNSUPPORTED;
     }
+    if (c->attn_prerotate < 0 || c->attn_prerotate > 2) { set_err(err, err_len, "attn_prerotate must be 0, 1 or 2"); return CA_ERR_INVALID_ARG; }
     if (c->attn_split < 0 || c->attn_split > 1) { set_err(err, err_len, "attn_split must be 0 or 1"); return CA_ERR_INVALID_ARG; }
     if (c->device < 0) { set_err(err, err_len, "device < 0"); return CA_ERR_INVALID_ARG; }
     return CA_OK;
@@ -438,6 +445,7 @@ void ca_destroy(ca_ctx *ctx) {
     if (ctx->save_slots) (void)hipFree(ctx->save_slots);
     if (ctx->rope) (void)hipFree(ctx->rope);
     if (ctx->partial) (void)hipFree(ctx->partial);
+    if (ctx->k_rot) (void)hipFree(ctx->k_rot);
     if (ctx->d_meta) (void)hipFree(ctx->d_meta);
     if (ctx->h_meta) (void)hipHostFree(ctx->h_meta);
     if (ctx->s_copy) (void)hipStreamDestroy(ctx->s_copy);
@@ -509,6 +517,10 @@ static ca_status create_impl(ca_ctx *ctx) {
         ctx->off_n_keep = off;  off = align_up(off + (size_t)c.max_seqs * 4, 256);
         ctx->off_cu_q = off;    off = align_up(off + ((size_t)c.max_seqs + 1) * 4, 256);
         ctx->off_cu_k = off;    off = align_up(off + ((size_t)c.max_seqs + 1) * 4, 256);
+        ctx->k_rot_pages = (size_t)c.max_batch_kv_tokens / c.page_size + (size_t)c.max_seqs;
+        ctx->off_dense0 = off;  off = align_up(off + (size_t)c.max_seqs * 4, 256);
+        ctx->off_rot_src = off; off = align_up(off + ctx->k_rot_pages * 4, 256);
+        ctx->off_rot_pos = off; off = align_up(off + ctx->k_rot_pages * 4, 256);
         ctx->off_combine = off; off = align_up(off + (size_t)kAttnMaxParts * sizeof(CombineItem), 256);
         ctx->off_items = off;   off = align_up(off + max_items_padded * sizeof(WorkItem), 256);
         ctx->upload_bytes = off;
@@ -525,6 +537,9 @@ static ca_status create_impl(ca_ctx *ctx) {
         const size_t bytes = (size_t)kAttnMaxParts * 256 * (size_t)(c.head_dim + 2) * sizeof(float);
         CA_HIP(ctx, hipMalloc((void **)&ctx->partial, bytes));
     }
+    const bool may_direct = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
+    if (may_direct && c.attn_prerotate != 1)
+        CA_HIP(ctx, hipMalloc((void **)&ctx->k_rot, ctx->k_rot_pages * (size_t)c.page_size * (size_t)row_bytes(c)));
     {
         hipDeviceProp_t prop;
         CA_HIP(ctx, hipGetDeviceProperties(&prop, c.device));
@@ -651,6 +666,28 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
             int most = 0;
             for (int i = 0; i < B; ++i) most = std::max(most, b->new_len[i] * G);
             tile = most > 128 ? 256 : 128;
+        }
+        const bool direct_for_rot = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
+        {   // rotate the keys once per layer when on average three or more row tiles would each rotate them
+            int64_t tiles256 = 0;
+            for (int i = 0; i < B; ++i) tiles256 += ((int64_t)b->new_len[i] * G + 255) / 256;
+            ctx->prerotate = ctx->k_rot && direct_for_rot && (c.attn_tile_rows == 0 || c.attn_tile_rows == 256) &&
+                             (c.attn_prerotate == 2 || (c.attn_prerotate == 0 && tiles256 >= (int64_t)3 * B));
+            if (ctx->prerotate) tile = 256;
+            int32_t *dense0 = (int32_t *)(ctx->h_meta + ctx->off_dense0);
+            int32_t *rot_src = (int32_t *)(ctx->h_meta + ctx->off_rot_src), *rot_pos = (int32_t *)(ctx->h_meta + ctx->off_rot_pos);
+            int32_t at = 0;
+            for (int i = 0; i < B; ++i) {
+                dense0[i] = at;
+                if (!ctx->prerotate) continue;
+                const int pages = (ctx->n_keep[i] + b->new_len[i] + c.page_size - 1) / c.page_size;
+                for (int p = 0; p < pages; ++p, ++at) {
+                    rot_src[at] = b->block_table[(int64_t)i * b->max_pages + p];
+                    rot_pos[at] = p * c.page_size;
+                }
+            }
+            if ((size_t)at > ctx->k_rot_pages) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_rope_rebase: internal: %d dense pages exceed %zu", at, ctx->k_rot_pages);
+            ctx->n_dense_pages = at;
         }
         ctx->tile_rows = tile;
         const bool direct_kernel = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
@@ -1140,6 +1177,13 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
     a.items = (const WorkItem *)(ctx->d_meta + ctx->off_items);
     a.combine = (const CombineItem *)(ctx->d_meta + ctx->off_combine);
     a.partial = ctx->partial;
+    a.k_rot = ctx->k_rot;
+    a.dense_page0 = (const int32_t *)(ctx->d_meta + ctx->off_dense0);
+    a.rot_src_page = (const int32_t *)(ctx->d_meta + ctx->off_rot_src);
+    a.rot_pos0 = (const int32_t *)(ctx->d_meta + ctx->off_rot_pos);
+    a.n_dense_pages = ctx->n_dense_pages;
+    a.prerotate = ctx->prerotate ? 1 : 0;
+    a.max_positions = c.max_positions;
     a.n_combine = ctx->n_combine;
     a.rope = ctx->rope;
     a.n_items = ctx->n_items;

@@ -144,9 +144,14 @@ def test_save_arbitrary_ranges_bit_exact(case):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [1, 3, 2], ids=["scalar", "staged", "direct"])
+def variant_config(variant):
+    """12 stands for the LDS-direct kernel (2) reading keys that were rotated once into a scratch copy"""
+    return dict(attn_variant=2, attn_prerotate=2) if variant == 12 else dict(attn_variant=variant)
+
+
+@pytest.mark.parametrize("variant", [1, 3, 2, 12], ids=["scalar", "staged", "direct", "direct-prerotated"])
 def test_attention_matches_oracle(case, variant):
-    run = GpuRun(case, tier="device", attn_variant=variant)
+    run = GpuRun(case, tier="device", **variant_config(variant))
     try:
         run.rebase()
         run.run_layer(0)
@@ -190,14 +195,14 @@ def test_small_batch_splits_keys_over_workgroups(shape, split):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [2, 3], ids=["direct", "staged"])
+@pytest.mark.parametrize("variant", [2, 3, 12], ids=["direct", "staged", "direct-prerotated"])
 def test_context_fills_the_largest_window_of_the_direct_kernel(variant):
     """One conversation whose context is exactly 32768 tokens: every entry of the LDS-direct kernel's page
     table is in use, the last tile ends on the window, positions reach 32767 (and the few row tiles of a
     single conversation are split over many workgroups)."""
     W, new = 32768, 200
     case = Case([W - new], [new], [0], 2, 1, 128, seed=29, window=W)
-    run = GpuRun(case, tier="device", attn_variant=variant)
+    run = GpuRun(case, tier="device", **variant_config(variant))
     try:
         run.rebase()
         run.run_layer(0)
@@ -225,7 +230,7 @@ def test_default_variant_follows_the_window(window):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [1, 3, 2], ids=["scalar", "staged", "direct"])
+@pytest.mark.parametrize("variant", [1, 3, 2, 12], ids=["scalar", "staged", "direct", "direct-prerotated"])
 def test_attention_peaky_softmax(variant):
     """Queries scaled x6: a handful of keys dominate each row and outputs are O(1), so a wrong key,
     a wrong mask edge or a wrong position cannot hide under the tolerance.  Scores grow with the
@@ -235,7 +240,7 @@ def test_attention_peaky_softmax(variant):
     i.e. with the kernel's first rounding point applied to both sides."""
     from synth import bf16_bits_to_f64, f32_to_bf16_bits
     case = Case([210, 64], [75, 130], [31, 0], 4, 2, 128, seed=11, q_scale=6.0)
-    run = GpuRun(case, tier="device", attn_variant=variant)
+    run = GpuRun(case, tier="device", **variant_config(variant))
     try:
         run.rebase()
         run.run_layer(0)

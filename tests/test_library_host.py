@@ -62,6 +62,7 @@ def test_config_default_and_struct_layout(lib):
     (dict(max_batch_q_tokens=1 << 20, max_batch_kv_tokens=1 << 10), "CA_ERR_OUT_OF_RANGE"),
     (dict(attn_variant=7), "CA_ERR_INVALID_ARG"),
     (dict(attn_split=2), "CA_ERR_INVALID_ARG"),
+    (dict(attn_prerotate=3), "CA_ERR_INVALID_ARG"),
     (dict(attn_variant=2, max_positions=65536), "CA_ERR_UNSUPPORTED"),
 ])
 def test_config_validation(lib, kw, status):
