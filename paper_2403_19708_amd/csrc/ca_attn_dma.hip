@@ -598,24 +598,22 @@ hipError_t launch_attn_dma(const AttnArgs &a, hipStream_t stream) {
     if (a.n_combine > 0 && (a.partial == nullptr || a.combine == nullptr)) return hipErrorInvalidValue;
     hipError_t e;
     if (a.prerotate) {
-        if (a.tile_rows != 256 || !a.k_rot || !a.dense_page0 || !a.rot_src_page || !a.rot_pos0 || a.n_dense_pages <= 0)
+        if ((a.tile_rows != 256 && a.tile_rows != 128) || !a.k_rot || !a.dense_page0 || !a.rot_src_page || !a.rot_pos0 || a.n_dense_pages <= 0)
             return hipErrorInvalidValue;
-        const dim3 rgrid(a.n_dense_pages, a.n_kv_heads), grid(a.n_items), block(512);
-        if (a.head_dim == 128 && a.rope_style == 0) {
-            hipLaunchKernelGGL((rotate_keys_kernel<128, 0>), rgrid, dim3(128), 0, stream, a);
-            hipLaunchKernelGGL((attn_dma_kernel<128, 0, 8, 64, false>), grid, block, 0, stream, a);
-        } else if (a.head_dim == 128) {
-            hipLaunchKernelGGL((rotate_keys_kernel<128, 1>), rgrid, dim3(128), 0, stream, a);
-            hipLaunchKernelGGL((attn_dma_kernel<128, 1, 8, 64, false>), grid, block, 0, stream, a);
-        } else if (a.head_dim == 64 && a.rope_style == 0) {
-            hipLaunchKernelGGL((rotate_keys_kernel<64, 0>), rgrid, dim3(64), 0, stream, a);
-            hipLaunchKernelGGL((attn_dma_kernel<64, 0, 8, 64, false>), grid, block, 0, stream, a);
-        } else if (a.head_dim == 64) {
-            hipLaunchKernelGGL((rotate_keys_kernel<64, 1>), rgrid, dim3(64), 0, stream, a);
-            hipLaunchKernelGGL((attn_dma_kernel<64, 1, 8, 64, false>), grid, block, 0, stream, a);
-        } else {
-            return hipErrorInvalidValue;
-        }
+        const dim3 rgrid(a.n_dense_pages, a.n_kv_heads), grid(a.n_items);
+        const bool big = a.tile_rows == 256;
+#define CA_LAUNCH_PREROT(DD, ST)                                                                              \
+        do {                                                                                                  \
+            hipLaunchKernelGGL((rotate_keys_kernel<DD, ST>), rgrid, dim3(DD), 0, stream, a);                 \
+            if (big) hipLaunchKernelGGL((attn_dma_kernel<DD, ST, 8, 64, false>), grid, dim3(512), 0, stream, a); \
+            else hipLaunchKernelGGL((attn_dma_kernel<DD, ST, 4, 32, false>), grid, dim3(256), 0, stream, a);  \
+        } while (0)
+        if (a.head_dim == 128 && a.rope_style == 0) CA_LAUNCH_PREROT(128, 0);
+        else if (a.head_dim == 128) CA_LAUNCH_PREROT(128, 1);
+        else if (a.head_dim == 64 && a.rope_style == 0) CA_LAUNCH_PREROT(64, 0);
+        else if (a.head_dim == 64) CA_LAUNCH_PREROT(64, 1);
+        else return hipErrorInvalidValue;
+#undef CA_LAUNCH_PREROT
         e = hipGetLastError();
     } else if (a.tile_rows == 256) e = launch_shape<8, 64>(a, stream);
     else if (a.tile_rows == 128) e = launch_shape<4, 32>(a, stream);

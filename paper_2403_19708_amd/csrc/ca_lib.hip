@@ -671,9 +671,9 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
         {   // rotate the keys once per layer when on average three or more row tiles would each rotate them
             int64_t tiles256 = 0;
             for (int i = 0; i < B; ++i) tiles256 += ((int64_t)b->new_len[i] * G + 255) / 256;
-            ctx->prerotate = ctx->k_rot && direct_for_rot && (c.attn_tile_rows == 0 || c.attn_tile_rows == 256) &&
+            ctx->prerotate = ctx->k_rot && direct_for_rot &&
                              (c.attn_prerotate == 2 || (c.attn_prerotate == 0 && tiles256 >= (int64_t)3 * B));
-            if (ctx->prerotate) tile = 256;
+            if (ctx->prerotate && c.attn_tile_rows == 0) tile = 256;
             int32_t *dense0 = (int32_t *)(ctx->h_meta + ctx->off_dense0);
             int32_t *rot_src = (int32_t *)(ctx->h_meta + ctx->off_rot_src), *rot_pos = (int32_t *)(ctx->h_meta + ctx->off_rot_pos);
             int32_t at = 0;

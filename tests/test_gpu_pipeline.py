@@ -17,10 +17,10 @@ def check_contract(got, want, where):
     assert err.max() <= 2e-2 and err.mean() <= 2e-3, (where, f"max-abs {err.max():.3e} mean-abs {err.mean():.3e}")
 
 
-def run_stack(case, tier, depth, mode, sync_every_op=False, tile=0, variant=0):
+def run_stack(case, tier, depth, mode, sync_every_op=False, tile=0, variant=0, **more):
     """Runs every layer the way the benchmark does: all loads queued first, then per layer
     append -> attention -> save.  Returns the outputs and the saved tier as bits."""
-    run = GpuRun(case, tier=tier, pipeline_depth=depth, load_mode=mode, attn_tile_rows=tile, attn_variant=variant)
+    run = GpuRun(case, tier=tier, pipeline_depth=depth, load_mode=mode, attn_tile_rows=tile, attn_variant=variant, **more)
     try:
         stream = torch.cuda.Stream()
         with torch.cuda.stream(stream):
@@ -100,11 +100,12 @@ def test_next_job_preloads_while_the_current_job_computes():
         a.close(); b.close()
 
 
-@pytest.mark.parametrize("variant", [3, 2], ids=["staged", "direct"])
+@pytest.mark.parametrize("variant", [3, 2, 12], ids=["staged", "direct", "direct-prerotated"])
 def test_both_tile_sizes_agree_with_oracle(variant):
     case = Case([500, 90], [200, 31], [37, 0], 8, 2, 128, seed=52)
+    more = dict(variant=2, attn_prerotate=2) if variant == 12 else dict(variant=variant)
     for tile in (128, 256):
-        out, _ = run_stack(case, "device", 2, 0, tile=tile, variant=variant)
+        out, _ = run_stack(case, "device", 2, 0, tile=tile, **more)
         at = 0
         for c in range(case.B):
             check_contract(bf16_bits_to_f64(out[0][at:at + int(case.new_len[c])]), case.oracle_out(0, c), (tile, c))
@@ -169,7 +170,7 @@ def test_multi_turn_reuse_with_truncation_equals_recompute():
             saved = saved + new
 
 
-@pytest.mark.parametrize("variant", [3, 2], ids=["staged", "direct"])
+@pytest.mark.parametrize("variant", [3, 2, 0], ids=["staged", "direct", "default"])
 @pytest.mark.parametrize("index", [2, 3, 4, 5])
 def test_full_size_layer_sampled_against_oracle(index, variant):
     """One layer at the benchmark's full shapes and length mix, in the launch configuration the
