@@ -47,7 +47,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-constexpr int NS = 4;     // LDS stages
 constexpr int kMaxPagesLds = 2048;   // page ids kept in LDS: contexts up to 32768 tokens
 
 __device__ inline float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
@@ -130,8 +129,10 @@ __device__ inline void rotate_dword(uint32_t &pa, uint32_t &pb, const float2 (&c
 // ROT = false: the keys come already rotated from a scratch copy of the context (rotate_keys_kernel below),
 // dense pages numbered per conversation; used when many row tiles share the keys of a (conversation, kv head)
 // and rotating them once beats rotating them in every tile.
-template <int D, int STYLE, int NW, int BN, bool ROT = true>
+// NS = LDS stages of the tile ring: the loads of tile T+NS-1 go out in iteration T.
+template <int D, int STYLE, int NW, int BN, bool ROT = true, int NS = 4>
 __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
+    static_assert(ROT ? NS >= 4 : NS >= 2, "the in-place rotary pass needs a tile landed one iteration early");
     constexpr int NTHREADS = 64 * NW;
     constexpr int MB = BN / 32;              // 32-key blocks of S^T per tile
     constexpr int KS2 = BN / 16;             // 16-key steps of the second product per tile
@@ -331,9 +332,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     // ---- prologue ---------------------------------------------------------------------------------------
     __syncthreads();                     // page ids are in LDS
     issue(t_begin);
-    if (t_begin + 1 < n_tiles) issue(t_begin + 1);
-    if (t_begin + 2 < n_tiles) issue(t_begin + 2);
-    if (t_begin + 2 < n_tiles) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }   // the first two tiles have landed
+    if (NS > 2 && t_begin + 1 < n_tiles) issue(t_begin + 1);
+    if (NS > 3 && t_begin + 2 < n_tiles) issue(t_begin + 2);
+    if (NS > 3 && t_begin + 2 < n_tiles) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }   // the first two tiles have landed
     __syncthreads();
     rot_read(ring + (t_begin % NS) * STAGE);
 #pragma unroll
@@ -447,7 +448,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 
         // tile+2 must have landed before anyone rotates it in the next iteration; the loads of tile+3
         // (issued at the top of this iteration) may stay in flight
-        if (INTERIOR) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }
+        if (INTERIOR && NS > 3) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }
         __syncthreads();
     };
 
