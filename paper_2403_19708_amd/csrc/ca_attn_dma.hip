@@ -551,7 +551,7 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a) {
 // Rotates the keys of the whole batch context once (Section 3.4: the rebased positional encoding, applied
 // when the cache is used): dense page dp of the scratch copy = pool page rot_src_page[dp] with token slot s
 // rotated at position rot_pos0[dp] + s, in fp32 from the table, rounded to bf16 -- the same values the fused
-// path forms tile by tile (there with the rotation advanced by recurrence).  blockIdx = (dense page, kv head);
+// path forms tile by tile (there with the rotation advanced by recurrence).  one workgroup per (dense page, kv head);
 // a thread owns one (token, pair of 16-byte pieces).  Slots past the end of a context hold whatever the pool
 // holds; nobody reads them.
 template <int D, int STYLE>
@@ -559,7 +559,11 @@ __global__ __launch_bounds__(D) void rotate_keys_kernel(AttnArgs a) {
     constexpr int HALF = D / 2;
     constexpr int PAIRS = D / 16;                       // piece pairs per row
     static_assert(kPageSize * PAIRS == D, "one thread per (token of the page, piece pair)");
-    const int dp = blockIdx.x, g = blockIdx.y;
+    // workgroup i runs on die i % 8: the heads of a page go to one die, one after the other, because they
+    // read the same 16 rows of the rotary table (its L2 then serves seven of the eight reads)
+    const int die = blockIdx.x % 8, k = blockIdx.x / 8;
+    const int dp = (k / a.n_kv_heads) * 8 + die, g = k % a.n_kv_heads;
+    if (dp >= a.n_dense_pages) return;
     const int key = threadIdx.x / PAIRS, pr = threadIdx.x % PAIRS;
     if (key >= kPageSize) return;
     const int pos = min(a.rot_pos0[dp] + key, a.max_positions - 1);
@@ -601,7 +605,7 @@ hipError_t launch_attn_dma(const AttnArgs &a, hipStream_t stream) {
     if (a.prerotate) {
         if ((a.tile_rows != 256 && a.tile_rows != 128) || !a.k_rot || !a.dense_page0 || !a.rot_src_page || !a.rot_pos0 || a.n_dense_pages <= 0)
             return hipErrorInvalidValue;
-        const dim3 rgrid(a.n_dense_pages, a.n_kv_heads), grid(a.n_items);
+        const dim3 rgrid((uint32_t)((a.n_dense_pages + 7) / 8) * 8u * (uint32_t)a.n_kv_heads), grid(a.n_items);
         const bool big = a.tile_rows == 256;
 #define CA_LAUNCH_PREROT(DD, ST)                                                                              \
         do {                                                                                                  \
