@@ -361,7 +361,22 @@ def main():
                    sample=f"attention of layer 0, conversations 0..{convs - 1} of {B} (all heads), {used:.1f} s of oracle time, "
                           f"scaled to {L} layers x {B} conversations by attention flops; data movement not included",
                    gflops=fl / used / 1e9)
-        log(f"[bench] oracle: {convs} conversations of one layer in {used:.1f}s on {cpu['cores']} threads")
+        # the oracle's plain unpack and pack loops on conversation 0 of layer 0 (K only), beside the move kernels
+        c0 = 0
+        rows = np.ascontiguousarray(np.concatenate([layer0["k_hist"][c0][int(keep_start[c0]):], layer0["k_new"][c0]]))
+        pool_cpu = np.zeros((num_pages, Hkv, 16, D), np.uint16)
+        back = np.zeros_like(rows)
+        tk = time.perf_counter()
+        oracle.unpack(rows, 0, pool_cpu, block_table[c0], 16, Hkv, D, 0, len(rows))
+        t_unpack = time.perf_counter() - tk
+        tk = time.perf_counter()
+        oracle.pack(pool_cpu, block_table[c0], 16, Hkv, D, 0, len(rows), back, 0)
+        t_pack = time.perf_counter() - tk
+        assert np.array_equal(back, rows)
+        cpu["move_gbs"] = {"unpack": 2.0 * rows.nbytes / t_unpack / 1e9, "pack": 2.0 * rows.nbytes / t_pack / 1e9,
+                           "sample": f"K of conversation {c0}, layer 0: {rows.nbytes / 1e6:.1f} MB each way, one thread"}
+        log(f"[bench] oracle: {convs} conversations of one layer in {used:.1f}s on {cpu['cores']} threads; "
+            f"unpack {cpu['move_gbs']['unpack']:.2f} GB/s, pack {cpu['move_gbs']['pack']:.2f} GB/s")
 
     result = {
         "metric": "cached-prefill tokens/s + attn TFLOP/s (% bf16 MFMA peak); KV load/pack GB/s",
