@@ -24,12 +24,14 @@ struct MoveArgs {
     int32_t seq[kMaxSeqsPerLaunch];  // row of the block table
 };
 
+constexpr int kMoveUnroll = 2;   // 16-byte loads in flight per lane of the move kernel (one pass = kMoveUnroll*256 vectors)
+
 struct MoveShape {
     const int32_t *block_table;  // device [n_seqs][max_pages]
     int32_t max_pages;
     int32_t n_kv_heads;
     int32_t vecs_per_row;        // head_dim * esize / 16
-    int32_t heads_per_wg;        // heads one workgroup moves (grid.z slices the heads)
+    int32_t heads_per_wg;        // heads one workgroup moves (grid.x slices the heads, and K/V)
     int32_t n_in_launch;
     int32_t max_pages_touched;   // largest number of pages a range of this launch touches
 };

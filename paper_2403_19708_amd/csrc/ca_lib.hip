@@ -894,8 +894,8 @@ ca_status run_move(ca_ctx *ctx, bool to_pool, const std::vector<Segment> &segs, 
     shape.max_pages = ctx->max_pages;
     shape.n_kv_heads = c.n_kv_heads;
     shape.vecs_per_row = c.head_dim * 2 / 16;
-    // one 256-lane pass of 4 x 16 bytes per lane and array covers 16 tokens x 16 KiB / (16 * row piece)
-    shape.heads_per_wg = std::max(1, std::min(c.n_kv_heads, 4 * 256 / (16 * shape.vecs_per_row)));
+    // one 256-lane pass of kMoveUnroll x 16 bytes per lane covers 16 tokens of this many heads
+    shape.heads_per_wg = std::max(1, std::min(c.n_kv_heads, kMoveUnroll * 256 / (16 * shape.vecs_per_row)));
     for (size_t at = 0; at < segs.size(); at += kMaxSeqsPerLaunch) {
         MoveArgs args;
         std::memset(&args, 0, sizeof args);
