@@ -47,11 +47,85 @@ def parse():
     ap.add_argument("--no-pipeline", action="store_true", help="skip the pinned-host (PCIe-inclusive) leg")
     ap.add_argument("--pipeline-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-phase leg (one new token per conversation, asynchronous write-back)")
+    ap.add_argument("--decode-steps", type=int, default=20)
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
     ap.add_argument("--load-mode", type=int, default=0, help="library load_mode for the pinned-host leg (0 staged copies, 2 kernels access the host tier in place)")
     ap.add_argument("--save-mode", type=int, default=0, help="library save_mode for the pinned-host leg")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging only; marks the result invalid)")
     return ap.parse_args()
+
+
+def decode_leg(torch, ca, cfg, n_steps, seed):
+    """Decode phase of a turn (Section 3.2.2) at the shape of the paper's saving experiment (Section 4.4:
+    batch 16, prompts of 1K..1.6K tokens, 20 decoding steps) on this workload's model: every step appends
+    one pre-rotary K/V token per conversation and layer, attends it over the whole context, and writes the
+    step's K/V back to the tier on the save stream while the next step runs.  The contexts are already in
+    the pool (as after the turn's prefill); the tier is device memory, as in the headline leg."""
+    from synth import draw_block_table
+    dev = torch.device("cuda:0")
+    L, Hq, Hkv, D = cfg["n_layers"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+    B = 16
+    rng = np.random.default_rng(seed + 77)
+    prompt = rng.integers(1000, 1601, B).astype(np.int32)
+    pages = (prompt + n_steps + P - 1) // P
+    num_pages = int(pages.sum()) + 4
+    bt = draw_block_table(pages, num_pages, seed + 78)
+    g = torch.Generator(device=dev); g.manual_seed(seed + 79)
+    randn = lambda shape: torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k_pool = [randn((num_pages, Hkv, P, D)) for _ in range(L)]
+    v_pool = [randn((num_pages, Hkv, P, D)) for _ in range(L)]
+    q = [randn((B, Hq, D)) for _ in range(L)]
+    kn = [randn((B, Hkv, D)) for _ in range(L)]
+    vn = [randn((B, Hkv, D)) for _ in range(L)]
+    out = [torch.zeros((B, Hq, D), dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    # tier rows of the generated tokens only (the prompt's rows were written by the prefill's save)
+    tier_k = [torch.zeros((B, n_steps, Hkv, D), dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    tier_v = [torch.zeros((B, n_steps, Hkv, D), dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    row = Hkv * D * 2
+    ptrs = lambda t: [t.data_ptr() + c * n_steps * row for c in range(B)]
+    tk_ptr = [ptrs(t) for t in tier_k]; tv_ptr = [ptrs(t) for t in tier_v]
+    conf = ca.Config(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=cfg["window"], max_seqs=B,
+                     max_batch_kv_tokens=int((prompt + n_steps).sum()) + 64, max_batch_q_tokens=B + 16, require_load=0)
+    scale = 1.0 / float(np.sqrt(D))
+    stream = torch.cuda.current_stream()
+    one, zero = np.ones(B, np.int32), np.zeros(B, np.int32)
+
+    def run(ctx, write_back):
+        host = 0.0
+        t0 = time.perf_counter()
+        for s in range(n_steps):
+            have = prompt + s
+            ctx.rope_rebase(have, zero, one, bt, num_pages, stream)
+            for l in range(L):
+                ctx.kv_append_layer(l, kn[l], vn[l], k_pool[l], v_pool[l], stream)
+                ctx.cached_prefill_attn(l, q[l], k_pool[l], v_pool[l], out[l], scale, stream)
+                if write_back:
+                    ctx.kv_save_layer(l, k_pool[l], v_pool[l], tk_ptr[l], tv_ptr[l], tok_begin=have, tok_end=have + 1,
+                                      dst_tok_offset=np.full(B, s, np.int64), after_stream=stream)
+        host = time.perf_counter() - t0
+        ctx.sync(); torch.cuda.synchronize()
+        return time.perf_counter() - t0, host
+
+    with ca.Context(conf) as ctx:
+        run(ctx, True)                                        # warm-up
+        t_plain, _ = run(ctx, False)
+        t_wb, host_wb = run(ctx, True)
+        ctx.profile_enable(True, ["attn"])
+        run(ctx, True)
+        att_ms, att_n = ctx.profile_read("attn")
+        ctx.profile_enable(False)
+        # the write-back must have delivered the pre-rotary bits of the last pass: spot check, layer 0
+        ok = bool(torch.equal(tier_k[0][:, -1], kn[0]) and torch.equal(tier_v[0][:, 0], vn[0]))
+    kv_bytes = 2.0 * float((prompt + (n_steps + 1) / 2.0).sum()) * row       # K and V of the mean context, per layer
+    att_us = att_ms / att_n * 1e3
+    return dict(batch=B, prompt_tokens=[int(prompt.min()), int(prompt.max())], steps=n_steps, layers=L,
+                ms_per_step=t_wb / n_steps * 1e3, tokens_per_s=B * n_steps / t_wb,
+                ms_per_step_without_write_back=t_plain / n_steps * 1e3, host_ms_per_step=host_wb / n_steps * 1e3,
+                attn_avg_launch_us=att_us, attn_kv_read_gbs=kv_bytes / att_us / 1e3,
+                attn_frac_hbm_peak=kv_bytes / att_us / 1e3 / HBM_PEAK_GBS, write_back_ok=ok,
+                note="one token per conversation and step through the same entry points; each step's K/V is written back "
+                     "on the save stream while the next step runs (device tier)")
 
 
 def main():
@@ -339,6 +413,17 @@ def main():
             log(f"[bench] pinned-host leg failed: {e!r}")
             pipeline = dict(error=repr(e))
 
+    # ---- leg 3: decode phase with asynchronous write-back -----------------------------------------------------
+    decode = None
+    if not args.no_decode:
+        try:
+            decode = decode_leg(torch, ca, dict(cfg, n_layers=L), args.decode_steps, args.seed)
+            log(f"[bench] decode leg: {decode['ms_per_step']:.2f} ms per step ({decode['ms_per_step_without_write_back']:.2f} without "
+                f"write-back), attention {decode['attn_avg_launch_us']:.1f} us, {decode['attn_kv_read_gbs']:.0f} GB/s of K/V")
+        except Exception as e:
+            log(f"[bench] decode leg failed: {e!r}")
+            decode = dict(error=repr(e))
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample --------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -410,6 +495,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "pipeline": pipeline,
+        "decode": decode,
         "parity": parity,
     }
     print(json.dumps(result), flush=True)
