@@ -70,15 +70,18 @@ class Store:
     def s_kv(self):
         return sum(i.size for i in self.items.values()) / len(self.items) if self.items else 0.0
 
+    def _window(self, capacity):
+        """floor(capacity / S_kv) with S_kv = total / count, in whole numbers: floor(capacity * count / total)"""
+        total = sum(i.size for i in self.items.values())
+        return (capacity * len(self.items)) // total if total > 0 else 0
+
     def prefetch_window(self):
         """L_pw = C_mem / S_kv (Section 3.3.1)"""
-        s = self.s_kv()
-        return int((self.mem_capacity - self.mem_buffer) // s) if s > 0 else 0
+        return self._window(self.mem_capacity - self.mem_buffer)
 
     def eviction_window(self):
         """(C_mem + C_disk) / S_kv (Section 3.3.2)"""
-        s = self.s_kv()
-        return int((self.mem_capacity - self.mem_buffer + self.disk_capacity) // s) if s > 0 else 0
+        return self._window(self.mem_capacity - self.mem_buffer + self.disk_capacity)
 
     def position(self, session):
         for p, s in enumerate(self.queue):

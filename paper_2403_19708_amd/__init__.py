@@ -1,6 +1,6 @@
 """MI355X-native hot path of CachedAttention (arXiv 2403.19708): thin Python binding over the
-C ABI in include/ca.h.  All computation happens in the HIP library; this package only marshals
-arguments.  Importing it does not load the library; the first call does, and fails loudly if the
+C ABI in include/ca.h, and over the placement manager in include/ca_store.h (module `store`).  All
+computation happens in the library; this package only marshals arguments.  Importing it does not load the library; the first call does, and fails loudly if the
 library has not been built (python -m paper_2403_19708_amd.build)."""
 from .binding import (  # noqa: F401
     CaError,

@@ -14,7 +14,8 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["ca_lib.hip", "ca_move.hip", "ca_attn_ref.hip", "ca_attn_mfma.hip", "ca_attn_dma.hip"]
+SOURCES = ["ca_lib.hip", "ca_move.hip", "ca_attn_ref.hip", "ca_attn_mfma.hip", "ca_attn_dma.hip",
+           "ca_store.cpp"]   # the last one is host code only (placement manager)
 LIB = os.path.join(HERE, "libca_hip.so")
 
 FLAGS = [
@@ -39,7 +40,8 @@ def is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     deps = [os.path.join(HERE, "csrc", s) for s in SOURCES]
-    deps += [os.path.join(HERE, "csrc", "ca_internal.h"), os.path.join(ROOT, "include", "ca.h")]
+    deps += [os.path.join(HERE, "csrc", "ca_internal.h"), os.path.join(ROOT, "include", "ca.h"),
+             os.path.join(ROOT, "include", "ca_store.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
