@@ -84,7 +84,7 @@ def decode_leg(torch, ca, cfg, n_steps, seed):
     tier_v = [torch.zeros((B, n_steps, Hkv, D), dtype=torch.bfloat16, device=dev) for _ in range(L)]
     row = Hkv * D * 2
     ptrs = lambda t: [t.data_ptr() + c * n_steps * row for c in range(B)]
-    tk_ptr = [ptrs(t) for t in tier_k]; tv_ptr = [ptrs(t) for t in tier_v]
+    tk_ptr = [ca.pointer_array(ptrs(t)) for t in tier_k]; tv_ptr = [ca.pointer_array(ptrs(t)) for t in tier_v]
     conf = ca.Config(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=cfg["window"], max_seqs=B,
                      max_batch_kv_tokens=int((prompt + n_steps).sum()) + 64, max_batch_q_tokens=B + 16, require_load=0)
     scale = 1.0 / float(np.sqrt(D))
@@ -96,13 +96,14 @@ def decode_leg(torch, ca, cfg, n_steps, seed):
         t0 = time.perf_counter()
         for s in range(n_steps):
             have = prompt + s
+            nxt, off = have + 1, np.full(B, s, np.int64)
             ctx.rope_rebase(have, zero, one, bt, num_pages, stream)
             for l in range(L):
                 ctx.kv_append_layer(l, kn[l], vn[l], k_pool[l], v_pool[l], stream)
                 ctx.cached_prefill_attn(l, q[l], k_pool[l], v_pool[l], out[l], scale, stream)
                 if write_back:
-                    ctx.kv_save_layer(l, k_pool[l], v_pool[l], tk_ptr[l], tv_ptr[l], tok_begin=have, tok_end=have + 1,
-                                      dst_tok_offset=np.full(B, s, np.int64), after_stream=stream)
+                    ctx.kv_save_layer(l, k_pool[l], v_pool[l], tk_ptr[l], tv_ptr[l], tok_begin=have, tok_end=nxt,
+                                      dst_tok_offset=off, after_stream=stream)
         host = time.perf_counter() - t0
         ctx.sync(); torch.cuda.synchronize()
         return time.perf_counter() - t0, host

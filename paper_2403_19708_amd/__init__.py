@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     config_validate,
     lib_path,
     load_library,
+    pointer_array,
     truncate_plan,
     truncate_plan_sinks,
 )

@@ -94,7 +94,8 @@ def load_library():
     lib.ca_kv_append_layer.restype = C.c_int
     lib.ca_cached_prefill_attn.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.c_float, vp]
     lib.ca_cached_prefill_attn.restype = C.c_int
-    lib.ca_kv_save_layer.argtypes = [vp, C.c_int32, i32p, i32p, vp, vp, C.POINTER(vp), C.POINTER(vp), i64p, vp]
+    # the three optional per-conversation arrays go in as plain addresses (cheaper to marshal per call)
+    lib.ca_kv_save_layer.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
     lib.ca_kv_save_layer.restype = C.c_int
     lib.ca_sync.argtypes = [vp]
     lib.ca_sync.restype = C.c_int
@@ -157,6 +158,14 @@ def _stream(s) -> int:
 def _i32(a):
     a = np.ascontiguousarray(a, dtype=np.int32)
     return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def pointer_array(ptrs):
+    """One pointer per conversation as the C array the load/save calls take.  The calls accept the result in
+    place of the list, so a caller that passes the same pointers again and again builds it once."""
+    if isinstance(ptrs, C.Array):
+        return ptrs
+    return (C.c_void_p * len(ptrs))(*[_ptr(p) or None for p in ptrs])
 
 
 def _make_batch(hist_len, keep_start, new_len, block_table, num_pages, keep_ranges=None):
@@ -284,8 +293,7 @@ class Context:
 
     # ---- Section 3.2.1 ----------------------------------------------------------------------
     def _ptr_array(self, ptrs):
-        arr = (C.c_void_p * len(ptrs))(*[_ptr(p) or None for p in ptrs])
-        return arr
+        return pointer_array(ptrs)
 
     def kv_load_layer(self, layer: int, src_k, src_v, k_pool, v_pool):
         ak, av = self._ptr_array(src_k), self._ptr_array(src_v)
@@ -309,22 +317,15 @@ class Context:
         if self.n_seqs and (len(ak) != self.n_seqs or len(av) != self.n_seqs):
             raise ValueError("dst_k/dst_v need one pointer per conversation of the current plan")
         keep = []
-        def opt_i32(a):
+        def opt(a, dtype):
             if a is None:
                 return None
-            arr, p = _i32(a)
+            arr = np.ascontiguousarray(a, dtype=dtype)
             if arr.shape != (self.n_seqs,):
                 raise ValueError("per-conversation arrays must have n_seqs entries")
             keep.append(arr)
-            return p
-        tb, te = opt_i32(tok_begin), opt_i32(tok_end)
-        off = None
-        if dst_tok_offset is not None:
-            o = np.ascontiguousarray(dst_tok_offset, dtype=np.int64)
-            if o.shape != (self.n_seqs,):
-                raise ValueError("dst_tok_offset must have n_seqs entries")
-            keep.append(o)
-            off = o.ctypes.data_as(C.POINTER(C.c_int64))
+            return arr.ctypes.data
+        tb, te, off = opt(tok_begin, np.int32), opt(tok_end, np.int32), opt(dst_tok_offset, np.int64)
         self._check(self._lib.ca_kv_save_layer(self._h, int(layer), tb, te, _ptr(k_pool), _ptr(v_pool), ak, av,
                                                off, _stream(after_stream)))
 
