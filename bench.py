@@ -125,6 +125,7 @@ def decode_leg(torch, ca, cfg, n_steps, seed):
                 ms_per_step_without_write_back=t_plain / n_steps * 1e3, host_ms_per_step=host_wb / n_steps * 1e3,
                 attn_avg_launch_us=att_us, attn_kv_read_gbs=kv_bytes / att_us / 1e3,
                 attn_frac_hbm_peak=kv_bytes / att_us / 1e3 / HBM_PEAK_GBS, write_back_ok=ok,
+                attn_kernel="attn_decode_kernel" if Hq // Hkv <= 2 else "attn_dma_kernel",
                 note="one token per conversation and step through the same entry points; each step's K/V is written back "
                      "on the save stream while the next step runs (device tier)")
 

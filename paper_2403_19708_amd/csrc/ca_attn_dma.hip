@@ -624,6 +624,12 @@ hipError_t launch_attn_dma(const AttnArgs &a, hipStream_t stream) {
     else if (a.tile_rows == 128) e = launch_shape<4, 32>(a, stream);
     else return hipErrorInvalidValue;
     if (e != hipSuccess || a.n_combine <= 0) return e;
+    return launch_attn_combine(a, stream);
+}
+
+hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t stream) {
+    if (a.n_combine <= 0) return hipSuccess;
+    if (a.partial == nullptr || a.combine == nullptr) return hipErrorInvalidValue;
     const int rows_per_group = 256 / (a.head_dim / 4);
     hipLaunchKernelGGL(combine_kernel, dim3(a.n_combine, (a.tile_rows + rows_per_group - 1) / rows_per_group), dim3(256), 0, stream, a);
     return hipGetLastError();

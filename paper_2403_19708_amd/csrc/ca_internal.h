@@ -116,6 +116,12 @@ constexpr int kRopeMinRows = 256;       // the kernels read table rows below thi
 hipError_t launch_attn_mfma(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_ref(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_dma(const AttnArgs &args, hipStream_t stream);
+// merges the shares of split row tiles (args.combine) into args.out; used by every kernel that writes shares
+hipError_t launch_attn_combine(const AttnArgs &args, hipStream_t stream);
+// decode steps: every item has at most kAttnDecodeMaxRows stacked rows starting at row 0; streams K/V through
+// registers instead of matrix-core tiles
+constexpr int kAttnDecodeMaxRows = 2;
+hipError_t launch_attn_decode(const AttnArgs &args, int max_rows, hipStream_t stream);
 constexpr int kAttnDmaMaxPositions = 32768;   // page ids of one conversation are kept in LDS
 constexpr int kAttnMaxParts = 1024;           // shares of split row tiles per batch (sizes the partial-result buffer)
 constexpr int kAttnMaxPartsPerTile = 16;

@@ -48,6 +48,7 @@ struct ca_ctx {
     // current plan (host copies)
     bool has_plan = false;
     int32_t n_seqs = 0, max_pages = 0, num_pages = 0, n_items = 0, n_combine = 0, tile_rows = 128;
+    int32_t max_unit_rows = 0;   // most stacked query rows of any (conversation, kv head) of the plan
     int64_t total_q = 0, total_k = 0, total_n = 0;
     std::vector<int32_t> hist_len, new_len, n_keep, cu_q, cu_k;
     // kept saved tokens of conversation i: ranges keep_rng[keep_rng_at[i] .. keep_rng_at[i+1]) of (begin, end)
@@ -248,12 +249,12 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
         set_err(err, err_len, "save_mode (0..2) out of range");
         return CA_ERR_INVALID_ARG;
     }
-    if (c->load_mode < 0 || c->load_mode > 2 || c->attn_variant < 0 || c->attn_variant > 3) {
-        set_err(err, err_len, "load_mode (0..2) or attn_variant (0..3) out of range");
+    if (c->load_mode < 0 || c->load_mode > 2 || c->attn_variant < 0 || c->attn_variant > 4) {
+        set_err(err, err_len, "load_mode (0..2) or attn_variant (0..4) out of range");
         return CA_ERR_INVALID_ARG;
     }
-    if (c->attn_variant == 2 && c->max_positions > kAttnDmaMaxPositions) {
-        set_err(err, err_len, "attn_variant 2 needs max_positions <= %d", kAttnDmaMaxPositions);
+    if ((c->attn_variant == 2 || c->attn_variant == 4) && c->max_positions > kAttnDmaMaxPositions) {
+        set_err(err, err_len, "attn_variant %d needs max_positions <= %d", c->attn_variant, kAttnDmaMaxPositions);
         return CA_ERR_UNSUPPORTED;
     }
     if (c->attn_tile_rows != 0 && c->attn_tile_rows != 128 && c->attn_tile_rows != 256) {
@@ -454,6 +455,11 @@ void ca_destroy(ca_ctx *ctx) {
     delete ctx;
 }
 
+// the kernels that stage K/V through LDS without registers (and the decode kernel) serve windows whose page ids fit in LDS
+static bool direct_variant(const ca_config &c) {
+    return c.attn_variant == 2 || c.attn_variant == 4 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
+}
+
 static ca_status create_impl(ca_ctx *ctx) {
     const ca_config &c = ctx->cfg;
     int n_dev = 0;
@@ -532,12 +538,12 @@ static ca_status create_impl(ca_ctx *ctx) {
         CA_HIP(ctx, hipHostMalloc((void **)&ctx->h_meta, ctx->upload_bytes, hipHostMallocDefault));
     }
     // Partial results of row tiles whose keys are split over workgroups (only the LDS-direct kernel splits).
-    const bool may_split = c.attn_split == 0 && (c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions));
+    const bool may_split = c.attn_split == 0 && direct_variant(c);
     if (may_split) {
         const size_t bytes = (size_t)kAttnMaxParts * 256 * (size_t)(c.head_dim + 2) * sizeof(float);
         CA_HIP(ctx, hipMalloc((void **)&ctx->partial, bytes));
     }
-    const bool may_direct = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
+    const bool may_direct = direct_variant(c);
     if (may_direct && c.attn_prerotate != 1)
         CA_HIP(ctx, hipMalloc((void **)&ctx->k_rot, ctx->k_rot_pages * (size_t)c.page_size * (size_t)row_bytes(c)));
     {
@@ -662,12 +668,11 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
         // 256-row tiles (8 wavefronts) halve the K/V re-reads and the rotary work per row when a
         // (conversation, kv head) has more than 128 stacked rows; small turns keep 128-row tiles
         int tile = c.attn_tile_rows;
-        if (tile == 0) {
-            int most = 0;
-            for (int i = 0; i < B; ++i) most = std::max(most, b->new_len[i] * G);
-            tile = most > 128 ? 256 : 128;
-        }
-        const bool direct_for_rot = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
+        int most = 0;
+        for (int i = 0; i < B; ++i) most = std::max(most, b->new_len[i] * G);
+        ctx->max_unit_rows = most;
+        if (tile == 0) tile = most > 128 ? 256 : 128;
+        const bool direct_for_rot = direct_variant(c);
         {   // rotate the keys once per layer when on average three or more row tiles would each rotate them
             int64_t tiles256 = 0;
             for (int i = 0; i < B; ++i) tiles256 += ((int64_t)b->new_len[i] * G + 255) / 256;
@@ -690,7 +695,7 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
             ctx->n_dense_pages = at;
         }
         ctx->tile_rows = tile;
-        const bool direct_kernel = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
+        const bool direct_kernel = direct_variant(c);
         struct Unit { int32_t seq, head; int64_t work; };
         std::vector<Unit> units;
         units.reserve((size_t)B * c.n_kv_heads);
@@ -709,6 +714,9 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
         // a 256-row workgroup whose rows fill at most four wavefronts, one per SIMD, takes 0.72 of that per
         // tile; rotating Q, filling the load pipeline and the epilogue cost about three tiles).
         struct Item { WorkItem w; double cost; int32_t parent; };
+        // A plan of decode steps goes to the streaming kernel, which reaches its bandwidth with one workgroup
+        // per compute unit: shares (and the merge they need) only pay when there are fewer items than that.
+        const bool decode_plan = direct_kernel && c.attn_variant != 2 && !ctx->prerotate && most >= 1 && most <= kAttnDecodeMaxRows;
         auto item_cost = [&](int n_rows, int keys) {
             const double per_tile = (tile == 256 && n_rows <= 128) ? 0.72 : 1.0;
             return per_tile * ((keys + 63) / 64) + 3.0;
@@ -744,7 +752,7 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
         std::vector<int32_t> parts_of(n_parents, 1);
         int32_t n_split_parts = 0;          // shares that need a slot in the partial-result buffer
         const auto by_cost = [](const Item &x, const Item &y) { return x.cost > y.cost; };
-        if (ctx->partial && direct_kernel && n_live < (size_t)6 * ctx->n_cus) {
+        if (ctx->partial && direct_kernel && n_live < (size_t)(decode_plan ? 1 : 6) * ctx->n_cus) {
             const int bins = std::max(1, ctx->n_cus / kXcds) * (tile == 128 ? 2 : 1);
             std::vector<double> heap;
             for (int d = 0; d < kXcds; ++d) {
@@ -1198,9 +1206,19 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
     int iv;
     CA_HIP(ctx, prof_begin(ctx, kProfAttn, stream, &iv));
     // 0 picks the LDS-direct kernel whenever its page-id table holds the window
-    const bool direct = c.attn_variant == 2 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
+    const bool direct = direct_variant(c);
+    // a decode step (one or two stacked rows per (conversation, kv head)) is a matrix-vector product: streamed
+    const bool decode = direct && c.attn_variant != 2 && !ctx->prerotate && ctx->max_unit_rows >= 1 &&
+                        ctx->max_unit_rows <= kAttnDecodeMaxRows;
+    if (c.attn_variant == 4 && !decode) {
+        (void)prof_end(ctx, iv, stream);
+        return fail(ctx, CA_ERR_UNSUPPORTED, "ca_cached_prefill_attn: attn_variant 4 needs at most %d stacked rows per (conversation, kv head), the plan has %d",
+                    kAttnDecodeMaxRows, ctx->max_unit_rows);
+    }
     if (c.attn_variant == 1) {
         CA_HIP(ctx, launch_attn_ref(a, stream));
+    } else if (decode) {
+        CA_HIP(ctx, launch_attn_decode(a, ctx->max_unit_rows, stream));
     } else if (direct) {
         CA_HIP(ctx, launch_attn_dma(a, stream));
     } else {
