@@ -49,3 +49,36 @@ def test_random_batch_matches_oracle(seed):
                 assert np.array_equal(got[case.hist_len[c]:], case.tensor(0, f"{which}_new", c)), (seed, which, c)
     finally:
         run.close()
+
+
+def draw_decode_case(seed):
+    """every conversation brings one or two new tokens and the heads are grouped by two at most: the shape the
+    streaming decode kernel takes under the automatic choice"""
+    rng = np.random.default_rng(5000 + seed)
+    B = int(rng.integers(1, 9))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 1, 2]))
+    D = int(rng.choice([64, 128]))
+    style = int(rng.integers(0, 2))
+    hist = np.where(rng.random(B) < 0.15, 0, rng.integers(0, 3000, B)).astype(np.int32)
+    new = rng.integers(1, (2 // G) + 1, B).astype(np.int32)
+    keep = np.array([int(rng.integers(0, h + 1)) if rng.random() < 0.4 else 0 for h in hist], np.int32)
+    knobs = dict(attn_split=int(rng.integers(0, 2)), attn_variant=int(rng.choice([0, 4, 2])))
+    return Case(hist, new, keep, Hkv * G, Hkv, D, seed=6000 + seed, style=style, window=4096), knobs
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_decode_batch_matches_oracle(seed):
+    case, knobs = draw_decode_case(seed)
+    run = GpuRun(case, tier="device", **knobs)
+    try:
+        run.rebase()
+        run.run_layer(0)
+        run.finish()
+        for c in range(case.B):
+            check_contract(run.out_f64(0, c), case.oracle_out(0, c), (seed, knobs, c))
+            check_tight(run.out_f64(0, c), case.oracle_out(0, c), int(case.n_keep[c]), (seed, knobs, c))
+        for which, pool in (("k", run.k_pool[0]), ("v", run.v_pool[0])):
+            assert np.array_equal(torch_to_bits(pool), case.oracle_pool(0, which)), (seed, which)
+    finally:
+        run.close()
