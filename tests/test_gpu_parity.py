@@ -221,6 +221,27 @@ def test_context_fills_the_largest_window_of_the_direct_kernel(variant):
         run.close()
 
 
+def test_context_longer_than_one_launch_row_of_pages():
+    """A context of more than 32768 pages: the move kernels cap their launch at that many page columns and walk
+    the rest in a second trip.  Pool, saved tier and the single new token's attention must come out as for
+    any other length (window 2^20, so the register-staged kernel serves it)."""
+    hist = 32768 * 16 + 1000
+    case = Case([hist], [1], [0], 1, 1, 64, seed=31, window=1 << 20)
+    run = GpuRun(case, tier="device")
+    try:
+        run.rebase()
+        run.run_layer(0)
+        run.finish()
+        check_contract(run.out_f64(0, 0), case.oracle_out(0, 0), "long")
+        for which, pool, host in (("k", run.k_pool[0], run.host_k[0]), ("v", run.v_pool[0], run.host_v[0])):
+            assert np.array_equal(torch_to_bits(pool), case.oracle_pool(0, which)), which
+            got = torch_to_bits(host[0])
+            assert np.array_equal(got[:hist], case.tensor(0, f"{which}_hist", 0)), which
+            assert np.array_equal(got[hist:], case.tensor(0, f"{which}_new", 0)), which
+    finally:
+        run.close()
+
+
 @pytest.mark.parametrize("window", [4096, 65536], ids=["direct-by-default", "staged-beyond-32768"])
 def test_default_variant_follows_the_window(window):
     """attn_variant 0 takes the LDS-direct kernel while its page-id table holds the window and the
