@@ -213,8 +213,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 
     // ---- rotary pass: this thread's (key, piece pair) of every K tile ------------------------------
     const bool rot_active = ROT && (ROT_TASKS >= NTHREADS || tid < ROT_TASKS);
-    const int rot_kk = tid / (PPR / 2);
-    const int rot_pr = tid % (PPR / 2);
+    // 16 consecutive lanes take the KPC keys of a chunk times consecutive pieces = 16 consecutive 16-byte
+    // slots, so the 16-byte LDS accesses of the pass are free of bank conflicts (key-major lanes were 2-way)
+    const int rot_kk = (tid / (KPC * (PPR / 2))) * KPC + tid % KPC;
+    const int rot_pr = (tid / KPC) % (PPR / 2);
     const int rot_off = (rot_kk / KPC) * CH + (rot_pr * KPC + rot_kk % KPC) * 16;   // piece rot_pr; partner +512
     constexpr int ROT_PARTNER = (PPR / 2) * KPC * 16;
     float2 k_step[8], k_cs[8];
