@@ -22,7 +22,8 @@ The section leaves several points open; the readings taken here (the library tak
   * When an item leaves memory and the disks are full, the incoming item competes with the disk
     items under the same order and is itself dropped if it ranks last (scheduler-aware only).
   * A fetch never evicts an item whose job comes sooner than the job fetched for.
-  * The session of the running job is pinned in memory from lookup to save.
+  * The session of the running job is pinned in memory from lookup to save (or to release, for a job that
+    ends without saving).
 """
 from __future__ import annotations
 
@@ -255,6 +256,16 @@ class Store:
         i.pinned = False
         if not ok:
             self._evict_from_memory(session)
+        self._make_room(self.mem_buffer)
+
+    def release(self, session, now):
+        """a job ended without saving (cancelled, failed): its session is no longer held in memory by a running
+        job; the cache stays where it is and the free buffer is restored, now that the item may be moved"""
+        self._expire(now)
+        i = self.items.get(session)
+        if i is None:
+            return
+        i.pinned = False
         self._make_room(self.mem_buffer)
 
     def take_actions(self):

@@ -105,6 +105,44 @@ def test_lru_and_fifo_reduce_to_the_textbook_caches(seed):
         assert run_single_tier(pl.FIFO, trace, cap) == textbook_fifo(trace, cap)
 
 
+def test_a_job_that_ends_without_saving_releases_its_session():
+    # textbook LRU in which some accesses are read-only and abandoned: a hit still counts as a use, a miss
+    # inserts nothing; written out here, independent of the oracle
+    rng = np.random.default_rng(11)
+    trace = [int(x) for x in rng.zipf(1.4, 400) % 17]
+    aborted = [bool(x) for x in rng.random(400) < 0.3]
+    for cap in (1, 3, 6):
+        cache, want = collections.OrderedDict(), []
+        for s, ab in zip(trace, aborted):
+            want.append(s in cache)
+            if s in cache:
+                cache.move_to_end(s)
+            elif not ab:
+                if len(cache) == cap:
+                    cache.popitem(last=False)
+                cache[s] = True
+        st = pl.Store(cap, 0, 0, pl.LRU, prefetch=False)
+        got = []
+        for t, (s, ab) in enumerate(zip(trace, aborted)):
+            got.append(st.lookup(s, now=float(t)) != pl.MISS)
+            if ab:
+                st.release(s, now=float(t))
+            else:
+                st.save(s, 1, now=float(t))
+        assert got == want
+        assert not any(i.pinned for i in st.items.values())
+    # a session that was looked up and never saved nor released can never leave memory; released, it can
+    st = pl.Store(2, 0, 0, pl.LRU, prefetch=False)
+    st.save(1, 1, now=0.0); st.save(2, 1, now=1.0)
+    assert st.lookup(1, now=2.0) == pl.HIT_MEM
+    st.save(3, 1, now=3.0)                      # 1 is pinned: 2 has to go although 1 is older
+    assert st.where(1) == 1 and st.where(2) == 0  # bit 0: in memory
+    st.release(1, now=4.0)
+    st.save(4, 1, now=5.0); st.save(5, 1, now=6.0)
+    assert st.where(1) == 0
+    st.release(99, now=7.0)                     # unknown session: nothing happens
+
+
 def fewest_misses(trace, capacity):
     """optimal demand replacement by exhaustive search over every choice of victim"""
     best = [len(trace)]
