@@ -19,6 +19,7 @@
  *   ca_store_prefetch    whenever there is time to look ahead (after each queue change);
  *   ca_store_lookup      when a job starts; pins the session in memory;
  *   ca_store_save        when a job ends and its cache has been written back; unpins.
+ *   ca_store_release     when a job ends without saving; unpins.
  *
  * Readings of points the section leaves open (they are the manager's behaviour):
  *   - S_kv is the mean size of the items stored at that moment; window lengths are
@@ -111,13 +112,18 @@ ca_status ca_store_set_queue(ca_store *store, const int64_t *sessions, int32_t n
 ca_status ca_store_prefetch(ca_store *store, double now);
 
 /* A job starts.  *where = CA_STORE_MISS / _HIT_MEM / _HIT_DISK; a disk hit is loaded into
- * memory on the spot (evicting if needed).  The session stays pinned until ca_store_save. */
+ * memory on the spot (evicting if needed).  The session stays pinned until ca_store_save
+ * or ca_store_release. */
 ca_status ca_store_lookup(ca_store *store, int64_t session, double now, int32_t *where);
 
 /* A job ended: the session's cache, now `size` units, is in host memory (Section 3.2.2
  * wrote it there).  Any disk copy becomes stale and is forgotten.  Evicts to restore
  * mem_buffer.  CA_ERR_OUT_OF_RANGE if size > mem_capacity, CA_ERR_INVALID_ARG if size <= 0. */
 ca_status ca_store_save(ca_store *store, int64_t session, int64_t size, double now);
+
+/* A job ended WITHOUT saving (cancelled, failed, read-only): the session is no longer pinned;
+ * its cache stays where it is and mem_buffer is restored.  Unknown sessions are ignored. */
+ca_status ca_store_release(ca_store *store, int64_t session, double now);
 
 /* *tiers = tier bits of the session (0: unknown to the store). */
 ca_status ca_store_where(const ca_store *store, int64_t session, int32_t *tiers);

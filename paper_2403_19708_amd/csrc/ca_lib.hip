@@ -615,6 +615,9 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
         ctx->meta_in_flight = false;
     }
 
+    // from here on the host copy of the plan is rewritten: until the new metadata has been queued for upload
+    // the context has no usable plan (a failure below must not leave new host counts beside old device tables)
+    ctx->has_plan = false;
     ctx->hist_len.assign(b->hist_len, b->hist_len + B);
     ctx->keep_rng_at.assign(B + 1, 0);
     ctx->keep_rng.clear();
@@ -1098,9 +1101,12 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
     if (total > c.max_batch_kv_tokens) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_kv_save_layer: %lld tokens exceed a staging slot", (long long)total);
     const bool staged = c.save_mode == 1 || (c.save_mode == 0 && any_host);
 
-    // saving starts after the producer of this layer's K/V
+    // saving starts after the producer of this layer's K/V: the work queued on `after_stream`, and the load of
+    // this layer if one was issued (its unpack runs on an internal stream and may still be writing the pages a
+    // range of kept-history tokens reads)
     CA_HIP(ctx, hipEventRecord(ctx->ev_after, (hipStream_t)after_stream));
     CA_HIP(ctx, hipStreamWaitEvent(ctx->s_save, ctx->ev_after, 0));
+    if (ctx->loaded[layer]) CA_HIP(ctx, hipStreamWaitEvent(ctx->s_save, ctx->ev_ready[layer], 0));
 
     std::vector<Segment> segs;
     segs.reserve(B);

@@ -346,6 +346,16 @@ ca_status ca_store_save(ca_store *s, int64_t session, int64_t size, double now) 
     return CA_OK;
 }
 
+ca_status ca_store_release(ca_store *s, int64_t session, double now) {
+    if (!s) return CA_ERR_INVALID_ARG;
+    s->expire(now);
+    auto it = s->entries.find(session);
+    if (it == s->entries.end()) return CA_OK;
+    it->second.pinned = false;
+    (void)s->make_room(s->cfg.mem_buffer, -1, false, 0);
+    return CA_OK;
+}
+
 ca_status ca_store_where(const ca_store *s, int64_t session, int32_t *tiers) {
     if (!s || !tiers) return CA_ERR_INVALID_ARG;
     auto it = s->entries.find(session);

@@ -15,7 +15,7 @@ FETCH, LOAD, EVICT, RELEASE, DROP_DISK, DROP, EXPIRE = 1, 2, 3, 4, 5, 6, 7
 
 # every symbol include/ca_store.h declares
 SYMBOLS = ["ca_store_create", "ca_store_destroy", "ca_store_last_error", "ca_store_seed", "ca_store_set_queue",
-           "ca_store_prefetch", "ca_store_lookup", "ca_store_save", "ca_store_where", "ca_store_windows",
+           "ca_store_prefetch", "ca_store_lookup", "ca_store_save", "ca_store_release", "ca_store_where", "ca_store_windows",
            "ca_store_usage", "ca_store_stats_read", "ca_store_take_actions"]
 
 
@@ -54,6 +54,7 @@ def _lib():
         lib.ca_store_prefetch.argtypes = [vp, C.c_double]
         lib.ca_store_lookup.argtypes = [vp, C.c_int64, C.c_double, i32p]
         lib.ca_store_save.argtypes = [vp, C.c_int64, C.c_int64, C.c_double]
+        lib.ca_store_release.argtypes = [vp, C.c_int64, C.c_double]
         lib.ca_store_where.argtypes = [vp, C.c_int64, i32p]
         lib.ca_store_windows.argtypes = [vp, i64p, i64p]
         lib.ca_store_usage.argtypes = [vp, i64p, i64p, i64p]
@@ -110,6 +111,9 @@ class Store:
 
     def save(self, session, size, now):
         self._check(self._lib.ca_store_save(self._h, int(session), int(size), float(now)))
+
+    def release(self, session, now):
+        self._check(self._lib.ca_store_release(self._h, int(session), float(now)))
 
     def where(self, session) -> int:
         out = C.c_int32()

@@ -28,7 +28,7 @@ def test_library_exports_every_symbol_of_the_store_header(lib):
     text = open(os.path.join(ROOT, "include", "ca_store.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(ca_store_[a-z_0-9]+)\s*\(", text)))
-    assert len(names) == 13 and sorted(cs.SYMBOLS) == names
+    assert len(names) == 14 and sorted(cs.SYMBOLS) == names
     for n in names:
         assert hasattr(lib, n), n
     # the constants of the binding are the header's
@@ -69,6 +69,11 @@ class Both:
     def save(self, s, size, now):
         self.lib.save(s, size, now)
         self.ref.save(s, size, now)
+        self.compare()
+
+    def release(self, s, now):
+        self.lib.release(s, now)
+        self.ref.release(s, now)
         self.compare()
 
     def compare(self, sessions=None):
@@ -135,8 +140,11 @@ def test_random_traces_decision_by_decision(policy, seed):
             running.append(s)
             if len(running) >= int(rng.integers(1, 4)):
                 for r in running:
-                    sizes[r] = min(sizes[r] + int(rng.integers(0, 2)), min(mem, 6))
                     now += 0.25
+                    if rng.random() < 0.15:                     # the job is abandoned: nothing to write back
+                        both.release(r, now)
+                        continue
+                    sizes[r] = min(sizes[r] + int(rng.integers(0, 2)), min(mem, 6))
                     both.save(r, sizes[r], now)
                 running = []
         both.compare(range(n_sessions))
