@@ -212,6 +212,20 @@ ca_status ca_kv_append_layer(ca_ctx *ctx, int32_t layer, const void *new_k, cons
 ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, const void *k_pool,
                                  const void *v_pool, void *out, float softmax_scale, void *stream);
 
+/* The same call for callers that cannot allocate device memory or tolerate a library that does:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Identical
+ * arguments, kernels and results; the one scratch buffer the attention kernels use beyond inputs
+ * and outputs -- the partial results (fp32 sums, maxima, denominators) of row tiles whose keys the
+ * plan split over several workgroups -- is taken from a fixed 32 MiB array inside the library's
+ * code object (one copy per GPU, held until the process ends) instead of the context's buffer.
+ * The call allocates nothing and records no timing intervals.  A plan whose shares need more than
+ * 32 MiB (n_shares * tile_rows * (head_dim + 2) * 4 bytes) is refused with CA_ERR_OUT_OF_RANGE
+ * and nothing is launched.  Every call on a GPU, from any context, uses that GPU's one array:
+ * calls that overlap in time on one GPU race (serialise them on one stream); nothing in the array
+ * needs clearing between calls, every share is written before it is read.                      */
+ca_status ca_cached_prefill_attn_static(ca_ctx *ctx, int32_t layer, const void *q, const void *k_pool,
+                                        const void *v_pool, void *out, float softmax_scale, void *stream);
+
 /* ---- Section 3.2.2: asynchronous saving --------------------------------------------------- */
 /* Copies context tokens [tok_begin[c], tok_end[c]) of every conversation (host int32 arrays;
  * NULL means the new tokens [n_keep, n_keep+new_len)) out of the pools into dst_k[c] / dst_v[c]

@@ -22,7 +22,8 @@ STATUS = {0: "CA_OK", 1: "CA_ERR_INVALID_ARG", 2: "CA_ERR_OUT_OF_RANGE", 3: "CA_
 # every symbol include/ca.h declares
 SYMBOLS = ["ca_config_default", "ca_config_validate", "ca_batch_validate", "ca_create", "ca_destroy",
            "ca_last_error", "ca_status_string", "ca_truncate_plan", "ca_truncate_plan_sinks", "ca_rope_rebase", "ca_rebase_read",
-           "ca_kv_load_layer", "ca_kv_append_layer", "ca_cached_prefill_attn", "ca_kv_save_layer",
+           "ca_kv_load_layer", "ca_kv_append_layer", "ca_cached_prefill_attn", "ca_cached_prefill_attn_static",
+           "ca_kv_save_layer",
            "ca_sync", "ca_join", "ca_profile_enable", "ca_profile_read"]
 
 
@@ -94,6 +95,8 @@ def load_library():
     lib.ca_kv_append_layer.restype = C.c_int
     lib.ca_cached_prefill_attn.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.c_float, vp]
     lib.ca_cached_prefill_attn.restype = C.c_int
+    lib.ca_cached_prefill_attn_static.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.c_float, vp]
+    lib.ca_cached_prefill_attn_static.restype = C.c_int
     # the three optional per-conversation arrays go in as plain addresses (cheaper to marshal per call)
     lib.ca_kv_save_layer.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
     lib.ca_kv_save_layer.restype = C.c_int
@@ -309,6 +312,10 @@ class Context:
     def cached_prefill_attn(self, layer: int, q, k_pool, v_pool, out, softmax_scale: float, stream=None):
         self._check(self._lib.ca_cached_prefill_attn(self._h, int(layer), _ptr(q), _ptr(k_pool), _ptr(v_pool),
                                                      _ptr(out), float(softmax_scale), _stream(stream)))
+
+    def cached_prefill_attn_static(self, layer: int, q, k_pool, v_pool, out, softmax_scale: float, stream=None):
+        self._check(self._lib.ca_cached_prefill_attn_static(self._h, int(layer), _ptr(q), _ptr(k_pool), _ptr(v_pool),
+                                                            _ptr(out), float(softmax_scale), _stream(stream)))
 
     # ---- Section 3.2.2 ----------------------------------------------------------------------
     def kv_save_layer(self, layer: int, k_pool, v_pool, dst_k, dst_v, tok_begin=None, tok_end=None,

@@ -18,6 +18,15 @@
 
 using namespace ca;
 
+// Partial-result buffer of ca_cached_prefill_attn_static: lives in the code object (one copy per GPU the library
+// runs on, held until the process ends), so that entry point needs no allocation anywhere.  The name below is a
+// host-side stand-in, not a device address: host code uses the per-device pointer that hipGetSymbolAddress
+// returned (static_scratch_ptr), never the array itself.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *static_scratch_ptr[kMaxDevices] = {nullptr};   // [device ordinal], filled by ca_create with that device current
+
 struct ca_ctx {
     ca_config cfg{};
     hipStream_t s_copy = nullptr, s_unpack = nullptr, s_save = nullptr;
@@ -49,6 +58,8 @@ struct ca_ctx {
     bool has_plan = false;
     int32_t n_seqs = 0, max_pages = 0, num_pages = 0, n_items = 0, n_combine = 0, tile_rows = 128;
     int32_t max_unit_rows = 0;   // most stacked query rows of any (conversation, kv head) of the plan
+    int32_t n_split_parts = 0;   // shares of split row tiles of the plan (slots of the partial-result buffer in use)
+    float *static_partial = nullptr;   // this device's copy of the static scratch array (ca_cached_prefill_attn_static)
     int64_t total_q = 0, total_k = 0, total_n = 0;
     std::vector<int32_t> hist_len, new_len, n_keep, cu_q, cu_k;
     // kept saved tokens of conversation i: ranges keep_rng[keep_rng_at[i] .. keep_rng_at[i+1]) of (begin, end)
@@ -551,6 +562,15 @@ static ca_status create_impl(ca_ctx *ctx) {
         CA_HIP(ctx, hipGetDeviceProperties(&prop, c.device));
         ctx->n_cus = std::max(8, prop.multiProcessorCount);
     }
+    // address of this device's copy of the static scratch array (the device is current here)
+    if (c.device < kMaxDevices) {
+        if (!static_scratch_ptr[c.device]) {
+            void *p = nullptr;
+            CA_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            static_scratch_ptr[c.device] = p;
+        }
+        ctx->static_partial = (float *)static_scratch_ptr[c.device];
+    }
     return CA_OK;
 }
 
@@ -819,6 +839,7 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
             if (at != n_split_parts || at > kAttnMaxParts) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_rope_rebase: internal: %d shares numbered, %d planned", at, n_split_parts);
         }
         ctx->n_combine = n_combine;
+        ctx->n_split_parts = n_split_parts;
 
         size_t longest = 0;
         for (auto &v : per_die) longest = std::max(longest, v.size());
@@ -1158,9 +1179,10 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
 // ----------------------------------------------------------------------------------------------
 // Sections 2.1 / 3.1 / 3.4: attention of the new tokens
 // ----------------------------------------------------------------------------------------------
-ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, const void *k_pool, const void *v_pool,
-                                 void *out, float softmax_scale, void *stream_) {
-    if (!ctx) return CA_ERR_INVALID_ARG;
+// partial: where the shares of split row tiles go (the context's buffer, or the static scratch array);
+// timed: bracket the launch with profiling events when profiling is on (creating an event may allocate)
+static ca_status attn_impl(ca_ctx *ctx, int32_t layer, const void *q, const void *k_pool, const void *v_pool, void *out,
+                           float softmax_scale, void *stream_, float *partial, bool timed) {
     ca_status st = check_layer_plan(ctx, "ca_cached_prefill_attn", layer);
     if (st != CA_OK) return st;
     const ca_config &c = ctx->cfg;
@@ -1190,7 +1212,7 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
     a.q_seq = (const int32_t *)(ctx->d_meta + ctx->off_q_seq);
     a.items = (const WorkItem *)(ctx->d_meta + ctx->off_items);
     a.combine = (const CombineItem *)(ctx->d_meta + ctx->off_combine);
-    a.partial = ctx->partial;
+    a.partial = partial;
     a.k_rot = ctx->k_rot;
     a.dense_page0 = (const int32_t *)(ctx->d_meta + ctx->off_dense0);
     a.rot_src_page = (const int32_t *)(ctx->d_meta + ctx->off_rot_src);
@@ -1209,8 +1231,8 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
     a.rope_style = c.rope_style;
     a.tile_rows = ctx->tile_rows;
     a.softmax_scale = softmax_scale;
-    int iv;
-    CA_HIP(ctx, prof_begin(ctx, kProfAttn, stream, &iv));
+    int iv = -1;
+    if (timed) CA_HIP(ctx, prof_begin(ctx, kProfAttn, stream, &iv));
     // 0 picks the LDS-direct kernel whenever its page-id table holds the window
     const bool direct = direct_variant(c);
     // a decode step (one or two stacked rows per (conversation, kv head)) is a matrix-vector product: streamed
@@ -1232,6 +1254,26 @@ ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, cons
     }
     CA_HIP(ctx, prof_end(ctx, iv, stream));
     return CA_OK;
+}
+
+ca_status ca_cached_prefill_attn(ca_ctx *ctx, int32_t layer, const void *q, const void *k_pool, const void *v_pool,
+                                 void *out, float softmax_scale, void *stream) {
+    if (!ctx) return CA_ERR_INVALID_ARG;
+    return attn_impl(ctx, layer, q, k_pool, v_pool, out, softmax_scale, stream, ctx->partial, true);
+}
+
+ca_status ca_cached_prefill_attn_static(ca_ctx *ctx, int32_t layer, const void *q, const void *k_pool, const void *v_pool,
+                                        void *out, float softmax_scale, void *stream) {
+    if (!ctx) return CA_ERR_INVALID_ARG;
+    if (ctx->has_plan && ctx->n_split_parts > 0) {
+        if (!ctx->static_partial)
+            return fail(ctx, CA_ERR_UNSUPPORTED, "ca_cached_prefill_attn_static: no static scratch on device %d", ctx->cfg.device);
+        const size_t need = (size_t)ctx->n_split_parts * (size_t)ctx->tile_rows * (size_t)(ctx->cfg.head_dim + 2) * sizeof(float);
+        if (need > kStaticScratchBytes)
+            return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_cached_prefill_attn_static: the plan's %d shares of split row tiles need %zu bytes of "
+                        "partial results, the static scratch holds %zu", ctx->n_split_parts, need, kStaticScratchBytes);
+    }
+    return attn_impl(ctx, layer, q, k_pool, v_pool, out, softmax_scale, stream, ctx->static_partial, false);
 }
 
 // ----------------------------------------------------------------------------------------------
