@@ -2,15 +2,19 @@
 """Benchmark of the cached-prefill hot path on one MI355X.
 
 One "step" is one pass of the whole path over one batch of synthetic conversations, for every
-layer of the stack:  rebase (once)  ->  per layer: load kept history into the paged pool,
-append the new turn's K/V, fused rotary + causal attention of the new tokens, save the new
-turn's K/V (pre-rotary) back to the tier.
+layer of the stack:  rebase (once)  ->  per layer: load the kept history from the KV tier into the
+paged pool (read stream), append the new turn's K/V, fused rotary + causal attention of the new
+tokens, save the new turn's K/V (without positions) back to the tier (write stream).
 
-Headline (`value`): new-turn tokens per second of the whole stack with the KV tier RESIDENT IN
-HBM when the timed region starts (the tier buffers are device memory; the same entry points
-run, the load kernel reads the tier in place).  The PCIe-inclusive pipeline (tier in pinned host
-memory, hipMemcpyAsync on the library's copy stream overlapped with attention) is measured in a
-second, shorter leg and reported under "pipeline"; it is never `value`.
+Default workload: the largest one-GPU configuration (config 5, LLaMA-70B-shaped grouped-query
+attention, 80 layers, batch 64) with the KV tier where the method keeps it, in PINNED HOST memory
+(Section 3.2.1), streamed layer by layer over the host link while attention runs.  `value` = new
+tokens per second of that pipeline (sum of new tokens / step time).  Q, the new K/V, the pools and
+all metadata are resident in HBM when the timed region starts; the tier is not an input hand-over
+but the storage level the method loads from.  The same step with the tier placed in HBM (no host
+link) is reported under "hbm_resident_tier", each kernel alone under "isolated", smaller
+configurations under "configs", the read-buffer experiments of Sections 3.2.1 / 4.3.2 under
+"pipeline_depth_sweep" and "preload_sweep", the decode phase under "decode".
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -28,7 +32,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 P = 16
 
@@ -37,31 +41,423 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def release_pinned(torch):
+    """hands cached pinned host blocks back to the system (the boxes pin only so much at a time)"""
+    import gc
+    gc.collect()
+    fn = getattr(torch._C, "_host_emptyCache", None)
+    if fn is not None:
+        fn()
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload index 1..5 (default 2: LLaMA-7B shapes, batch 16)")
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=5, help="workload index 1..5 (default 5: LLaMA-70B-shaped GQA, 80 layers, batch 64)")
+    ap.add_argument("--tier", choices=["pinned", "hbm"], default="pinned",
+                    help="where the KV tier of the headline leg lives (pinned host memory is the method's tier)")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--no-pipeline", action="store_true", help="skip the pinned-host (PCIe-inclusive) leg")
-    ap.add_argument("--pipeline-steps", type=int, default=3)
+    ap.add_argument("--hbm-steps", type=int, default=3, help="timed steps of the HBM-resident-tier leg")
+    ap.add_argument("--summary-configs", type=str, default="2,3,4", help="configurations for the compact per-config summary ('' = none)")
+    ap.add_argument("--no-hbm-leg", action="store_true")
+    ap.add_argument("--no-sweeps", action="store_true", help="skip the pipeline-depth and preload sweeps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-decode", action="store_true", help="skip the decode-phase leg (one new token per conversation, asynchronous write-back)")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-phase leg")
     ap.add_argument("--decode-steps", type=int, default=20)
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
-    ap.add_argument("--load-mode", type=int, default=0, help="library load_mode for the pinned-host leg (0 staged copies, 2 kernels access the host tier in place)")
-    ap.add_argument("--save-mode", type=int, default=0, help="library save_mode for the pinned-host leg")
+    ap.add_argument("--load-mode", type=int, default=0, help="library load_mode (0 staged copies for a host tier, 2 kernels read the tier in place)")
+    ap.add_argument("--save-mode", type=int, default=0)
+    ap.add_argument("--depth", type=int, default=2, help="staging slots of the read stream (pipeline_depth) in the headline leg")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging only; marks the result invalid)")
     return ap.parse_args()
 
 
+# ----------------------------------------------------------------------------------------------------
+# one workload on the device
+# ----------------------------------------------------------------------------------------------------
+class Job:
+    """Device (and optionally pinned-host) tensors of one batch of conversations for every layer, and the
+    step that drives them through the library.  Layer 0 carries the seeded bits of synth/ (so that sampled
+    outputs can be checked against the oracle); the other layers are filled by the device generator:
+    distinct buffers per layer, so all traffic is real."""
+
+    def __init__(self, torch, ca, index, seed, layers=0, with_layer0_bits=True, lengths=None, model=None):
+        from synth import CONFIGS, draw_block_table, draw_values_bf16, make_workload
+        self.torch, self.ca = torch, ca
+        self.dev = torch.device("cuda:0")
+        if lengths is None:
+            wl = make_workload(index, seed=seed)
+            cfg, hist, new = wl.cfg, wl.hist_len, wl.new_len
+            self.wl = wl
+        else:                                   # fixed lengths on a configuration's model shape
+            cfg = dict(CONFIGS[model]); hist, new = lengths
+            cfg["batch"] = len(hist); cfg["truncate"] = False
+            self.wl = None
+            with_layer0_bits = False
+        self.cfg, self.index, self.seed = cfg, index, seed
+        self.L = layers or cfg["n_layers"]
+        self.Hq, self.Hkv, self.D, self.B, self.W = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["batch"], cfg["window"]
+        self.hist, self.new = hist, new
+        self.keep_start = ca.truncate_plan(hist, new, self.W, cfg["ratio"], policy=0) if cfg["truncate"] else np.zeros(self.B, np.int32)
+        self.n_keep = hist - self.keep_start
+        self.ctx_len = self.n_keep + new
+        pages = (self.ctx_len + P - 1) // P
+        self.num_pages = int(pages.sum()) + 8
+        self.block_table = draw_block_table(pages, self.num_pages, seed + 17)
+        self.tot_q, self.tot_n, self.tot_k = int(new.sum()), int(self.n_keep.sum()), int(self.ctx_len.sum())
+        self.cu_q = np.concatenate([[0], np.cumsum(new)]).astype(np.int64)
+        self.row = self.Hkv * self.D            # elements per token on the KV side
+        self.scale = 1.0 / float(np.sqrt(self.D))
+        # algorithmic work per layer = one launch of each kernel
+        newf, keepf = new.astype(np.float64), self.n_keep.astype(np.float64)
+        self.flops_layer = 4.0 * self.D * self.Hq * float(np.sum(newf * keepf + newf * (newf + 1) / 2))
+        self.attn_bytes = 2.0 * self.tot_k * self.row * 2 + 2.0 * self.tot_q * self.Hq * self.D * 2   # K,V once + Q in + O out
+        self.unpack_bytes = 2.0 * (2.0 * self.tot_n * self.row * 2)                                   # read + write, K and V
+        self.append_bytes = 2.0 * (2.0 * self.tot_q * self.row * 2)
+        self.pack_bytes = 2.0 * (2.0 * self.tot_q * self.row * 2)
+        self.link_in_bytes = 2.0 * self.tot_n * self.row * 2
+        self.link_out_bytes = 2.0 * self.tot_q * self.row * 2
+        self.t_mfma_us = self.flops_layer / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6
+        self.t_hbm_us = self.attn_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
+        self.attn_bound = "mfma" if self.t_mfma_us > self.t_hbm_us else "hbm"
+        self.attn_floor_us = max(self.t_mfma_us, self.t_hbm_us)
+
+        gen = torch.Generator(device=self.dev)
+        gen.manual_seed(1234 + seed + 1000 * index)
+        self._gen = gen
+        L, B = self.L, self.B
+        self.tier_off = np.concatenate([[0], np.cumsum(hist.astype(np.int64) + new)])
+        self.layer0 = {}
+        if with_layer0_bits:
+            for name, toks in (("k_hist", hist), ("v_hist", hist), ("q", new), ("k_new", new), ("v_new", new)):
+                heads = self.Hq if name == "q" else self.Hkv
+                self.layer0[name] = [draw_values_bf16((int(toks[c]), heads, self.D), seed, self.wl.stream(0, name, c)) for c in range(B)]
+        self.k_pool, self.v_pool, self.q, self.k_new, self.v_new, self.out = [], [], [], [], [], []
+        bf = torch.bfloat16
+        for l in range(L):
+            if l == 0 and with_layer0_bits:
+                self.q.append(self.bits_to_dev(np.concatenate(self.layer0["q"])))
+                self.k_new.append(self.bits_to_dev(np.concatenate(self.layer0["k_new"])))
+                self.v_new.append(self.bits_to_dev(np.concatenate(self.layer0["v_new"])))
+            else:
+                self.q.append(self.randn((self.tot_q, self.Hq, self.D)))
+                self.k_new.append(self.randn((self.tot_q, self.Hkv, self.D)))
+                self.v_new.append(self.randn((self.tot_q, self.Hkv, self.D)))
+            self.k_pool.append(torch.zeros((self.num_pages, self.Hkv, P, self.D), dtype=bf, device=self.dev))
+            self.v_pool.append(torch.zeros((self.num_pages, self.Hkv, P, self.D), dtype=bf, device=self.dev))
+            self.out.append(torch.zeros((self.tot_q, self.Hq, self.D), dtype=bf, device=self.dev))
+        self.dev_tier = None
+        self.pin_tier = None
+
+    def bits_to_dev(self, bits):
+        t = self.torch
+        return t.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(t.bfloat16).to(self.dev)
+
+    def randn(self, shape):
+        t = self.torch
+        return t.randn(shape, generator=self._gen, device=self.dev, dtype=t.float32).to(t.bfloat16)
+
+    def _fill_tier_layer(self, l, tk, tv):
+        """values of the tier of layer l into the device tensors tk, tv ([all conversations' hist+new tokens][Hkv][D])"""
+        if l == 0 and self.layer0:
+            tk.zero_(); tv.zero_()
+            for c in range(self.B):
+                a = int(self.tier_off[c])
+                tk[a:a + int(self.hist[c])] = self.bits_to_dev(self.layer0["k_hist"][c])
+                tv[a:a + int(self.hist[c])] = self.bits_to_dev(self.layer0["v_hist"][c])
+        else:
+            tk.copy_(self.randn(tk.shape)); tv.copy_(self.randn(tv.shape))
+
+    def make_device_tier(self):
+        t = self.torch
+        shape = (int(self.tier_off[-1]), self.Hkv, self.D)
+        self.dev_tier = ([], [])
+        for l in range(self.L):
+            tk = t.empty(shape, dtype=t.bfloat16, device=self.dev); tv = t.empty_like(tk)
+            self._fill_tier_layer(l, tk, tv)
+            self.dev_tier[0].append(tk); self.dev_tier[1].append(tv)
+        t.cuda.synchronize()
+
+    def make_pinned_tier(self, cap_gib=40.0):
+        """The tier in pinned host memory, one K and one V buffer per layer (filled through the device).  The
+        boxes refuse to pin much more than ~50 GiB: when the whole stack does not fit under cap_gib (or pinning
+        fails earlier), the layers cycle through the n_distinct buffers that could be pinned (layer l uses buffer
+        l % n_distinct); every byte still crosses the host link, from distinct memory within any window of
+        n_distinct layers."""
+        t = self.torch
+        shape = (int(self.tier_off[-1]), self.Hkv, self.D)
+        per_layer = 2 * int(self.tier_off[-1]) * self.row * 2
+        want = max(1, min(self.L, int(cap_gib * 2**30 // per_layer)))
+        pk_list, pv_list = [], []
+        tk = t.empty(shape, dtype=t.bfloat16, device=self.dev); tv = t.empty_like(tk)
+        t0 = time.time()
+        for l in range(want):
+            try:
+                pk = t.empty(shape, dtype=t.bfloat16, pin_memory=True); pv = t.empty(shape, dtype=t.bfloat16, pin_memory=True)
+            except Exception as e:                     # the box will not pin more: keep a margin and cycle
+                log(f"[bench]   pinning stopped at layer {l}: {type(e).__name__}")
+                for lst in (pk_list, pv_list):
+                    del lst[-2:]
+                release_pinned(t)
+                try:                                   # the refused allocation may leave its error to the next call
+                    t.cuda.synchronize()
+                except Exception:
+                    pass
+                break
+            if self.dev_tier is not None:
+                sk, sv = self.dev_tier[0][l], self.dev_tier[1][l]
+            else:
+                self._fill_tier_layer(l, tk, tv); sk, sv = tk, tv
+            pk.copy_(sk); pv.copy_(sv)
+            pk_list.append(pk); pv_list.append(pv)
+        t.cuda.synchronize()
+        del tk, tv
+        n = len(pk_list)
+        if n == 0:
+            raise RuntimeError("no pinned host memory available")
+        self.pin_distinct = n
+        self.pin_gib = n * per_layer / 2**30
+        self.pin_tier = ([pk_list[l % n] for l in range(self.L)], [pv_list[l % n] for l in range(self.L)])
+        log(f"[bench]   pinned tier: {n} distinct layer buffers of {self.L} layers, {self.pin_gib:.1f} GiB, {time.time() - t0:.1f}s")
+
+    def tier_ptrs(self, bufs):
+        """per layer, the library's pointer array of the conversations' saved token 0"""
+        esz = self.row * 2
+        return [self.ca.pointer_array([bufs[l].data_ptr() + int(self.tier_off[c]) * esz for c in range(self.B)]) for l in range(self.L)]
+
+    def config(self, **kw):
+        base = dict(n_layers=self.L, n_q_heads=self.Hq, n_kv_heads=self.Hkv, head_dim=self.D, max_positions=self.W, pipeline_depth=2,
+                    max_seqs=self.B, max_batch_kv_tokens=self.tot_k + 64, max_batch_q_tokens=self.tot_q + 16)
+        base.update(kw)
+        return self.ca.Config(**base)
+
+    def rebase(self, ctx, stream):
+        ctx.rope_rebase(self.hist, self.keep_start, self.new, self.block_table, self.num_pages, stream)
+
+    def compute_layer(self, ctx, l, src_k, src_v, stream, save=True):
+        ctx.kv_append_layer(l, self.k_new[l], self.v_new[l], self.k_pool[l], self.v_pool[l], stream)
+        ctx.cached_prefill_attn(l, self.q[l], self.k_pool[l], self.v_pool[l], self.out[l], self.scale, stream)
+        if save:
+            ctx.kv_save_layer(l, self.k_pool[l], self.v_pool[l], src_k[l], src_v[l], after_stream=stream)
+
+    def step(self, ctx, src_k, src_v, stream):
+        """the whole path for one batch: the read stream runs ahead as far as its staging slots allow"""
+        self.rebase(ctx, stream)
+        for l in range(self.L):
+            ctx.kv_load_layer(l, src_k[l], src_v[l], self.k_pool[l], self.v_pool[l])
+        for l in range(self.L):
+            self.compute_layer(ctx, l, src_k, src_v, stream)
+        ctx.join(stream)
+
+    def timed(self, ctx, src_k, src_v, stream, warmup, steps, tag, kinds=None):
+        """kinds: which of the library's kernels/copies are bracketed by HIP events during the timed steps
+        (None = all; the events cost a few per cent of a step made of short kernels)"""
+        torch, ca = self.torch, self.ca
+        for _ in range(warmup):
+            self.step(ctx, src_k, src_v, stream)
+        ctx.sync(); torch.cuda.synchronize()
+        for k in ca.Context.PROFILE_KINDS:
+            ctx.profile_read(k)              # drop what the warm-up recorded
+        ctx.profile_enable(True, kinds)
+        t = time.perf_counter()
+        for _ in range(steps):
+            self.step(ctx, src_k, src_v, stream)
+        ctx.sync(); torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        ctx.profile_enable(False)
+        prof = {k: ctx.profile_read(k) for k in ca.Context.PROFILE_KINDS}
+        log(f"[bench] {tag}: {steps} steps in {dt * 1e3:.1f} ms")
+        return dt, prof
+
+    def isolated(self, ctx, src_k, src_v, stream):
+        """each kernel alone (nothing else on the GPU), a few layers"""
+        torch = self.torch
+        n_iso = min(self.L, 4)
+        for k in self.ca.Context.PROFILE_KINDS:
+            ctx.profile_read(k)
+        ctx.profile_enable(True)
+        sync = lambda: (ctx.sync(), torch.cuda.synchronize())
+        for l in range(n_iso):
+            sync(); self.rebase(ctx, stream)
+            sync(); ctx.kv_load_layer(l, src_k[l], src_v[l], self.k_pool[l], self.v_pool[l])
+            sync(); ctx.kv_append_layer(l, self.k_new[l], self.v_new[l], self.k_pool[l], self.v_pool[l], stream)
+            sync(); ctx.cached_prefill_attn(l, self.q[l], self.k_pool[l], self.v_pool[l], self.out[l], self.scale, stream)
+            sync(); ctx.kv_save_layer(l, self.k_pool[l], self.v_pool[l], src_k[l], src_v[l], after_stream=stream)
+            sync()
+        ctx.profile_enable(False)
+        iso = {}
+        for kname, nbytes in (("attn", self.attn_bytes), ("unpack", self.unpack_bytes), ("append", self.append_bytes), ("pack", self.pack_bytes)):
+            ms, cnt = ctx.profile_read(kname)
+            us = ms / cnt * 1e3 if cnt else None
+            iso[kname] = {"avg_launch_us": us, "gbs": nbytes / (us * 1e-6) / 1e9 if us else None,
+                          "frac_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS if us else None}
+        for k in ("copy_in", "copy_out"):
+            ctx.profile_read(k)
+        a = iso["attn"]
+        a["tflops"] = self.flops_layer / (a["avg_launch_us"] * 1e-6) / 1e12
+        a["frac_mfma_peak"] = a["tflops"] / MFMA_BF16_PEAK_TFLOPS
+        a["binding_roofline"] = self.attn_bound
+        a["roofline_floor_us"] = self.attn_floor_us
+        a["frac_binding_roofline"] = self.attn_floor_us / a["avg_launch_us"]
+        return iso
+
+    def attn_figures(self, us):
+        tf = self.flops_layer / (us * 1e-6) / 1e12
+        gbs = self.attn_bytes / (us * 1e-6) / 1e9
+        return {"avg_launch_us": us, "tflops": tf, "frac_mfma_peak": tf / MFMA_BF16_PEAK_TFLOPS, "gbs": gbs,
+                "frac_hbm_peak": gbs / HBM_PEAK_GBS, "binding_roofline": self.attn_bound, "roofline_floor_us": self.attn_floor_us,
+                "frac_binding_roofline": self.attn_floor_us / us}
+
+    def move_figures(self, prof):
+        out = {}
+        for k, nbytes in (("unpack", self.unpack_bytes), ("append", self.append_bytes), ("pack", self.pack_bytes)):
+            ms, n = prof[k]
+            us = ms / n * 1e3 if n else None
+            out[k] = {"avg_launch_us": us, "gbs": nbytes / (us * 1e-6) / 1e9 if us else None,
+                      "frac_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS if us else None}
+        return out
+
+    def parity(self, layer0_out):
+        """sampled (conversation, head) outputs of layer 0 against the oracle, element by element"""
+        import oracle
+        from synth import bf16_bits_to_f64 as w
+        torch = self.torch
+        got_all = layer0_out.detach().cpu().view(torch.int16).numpy().view(np.uint16)
+        rng = np.random.default_rng(5)
+        samples = [(int(rng.integers(self.B)), int(rng.integers(self.Hq))) for _ in range(6)]
+        G = self.Hq // self.Hkv
+        worst_max, worst_mean = 0.0, 0.0
+        l0 = self.layer0
+        for c, h in samples:
+            g = h // G
+            want = oracle.cached_attention(w(l0["k_hist"][c][:, g:g + 1]), w(l0["v_hist"][c][:, g:g + 1]), w(l0["q"][c][:, h:h + 1]),
+                                           w(l0["k_new"][c][:, g:g + 1]), w(l0["v_new"][c][:, g:g + 1]), keep_start=int(self.keep_start[c]))
+            got = w(got_all[int(self.cu_q[c]):int(self.cu_q[c + 1]), h:h + 1])
+            err = np.abs(got - want)
+            worst_max, worst_mean = max(worst_max, float(err.max())), max(worst_mean, float(err.mean()))
+        ok = bool(worst_max <= 2e-2 and worst_mean <= 2e-3)
+        log(f"[bench] sampled parity vs oracle (layer 0): max-abs {worst_max:.2e} mean-abs {worst_mean:.2e}")
+        return dict(samples=len(samples), max_abs=worst_max, mean_abs=worst_mean, ok=ok)
+
+    def free(self):
+        for name in ("k_pool", "v_pool", "q", "k_new", "v_new", "out"):
+            setattr(self, name, None)
+        self.dev_tier = self.pin_tier = None
+        self.torch.cuda.empty_cache()
+        release_pinned(self.torch)
+
+
+# ----------------------------------------------------------------------------------------------------
+# legs
+# ----------------------------------------------------------------------------------------------------
+def pipeline_figures(job, dt, steps, prof):
+    """Section 3.2.1's quantities from the events of the timed steps of a host-tier run"""
+    t_pipe = dt / steps
+    cin_ms, cin_n = prof["copy_in"]; cout_ms, cout_n = prof["copy_out"]; att_ms, att_n = prof["attn"]
+    t_in, t_out, t_attn = cin_ms / steps / 1e3, cout_ms / steps / 1e3, att_ms / steps / 1e3
+    L = job.L
+    # per token and layer, as the paper defines them: T_load = access time of one token's K/V, T_pref = prefill
+    # time of one new token (here: its attention, the only compute on this path)
+    t_load_tok = t_in / L / max(job.tot_n, 1)
+    t_pref_tok = t_attn / L / max(job.tot_q, 1)
+    lhs, rhs = t_load_tok * job.tot_n, t_pref_tok * job.tot_q        # = per-layer load time, per-layer compute time
+    link_gbs = job.link_in_bytes * cin_n / (cin_ms * 1e-3) / 1e9 if cin_ms else None
+    s_buf = (link_gbs or 0.0) * 1e9 * max(0.0, lhs - rhs) * L        # bytes for the whole stack
+    return dict(
+        ms_per_step=t_pipe * 1e3, tokens_per_s=job.tot_q / t_pipe, context_tokens_per_s=job.tot_k / t_pipe,
+        h2d_gbs=link_gbs, d2h_gbs=job.link_out_bytes * cout_n / (cout_ms * 1e-3) / 1e9 if cout_ms else None,
+        copy_in_ms=t_in * 1e3, copy_out_ms=t_out * 1e3, attn_ms=t_attn * 1e3,
+        # (T_copy + T_attn - T_pipe) / min(T_copy, T_attn): 1.0 = the shorter one is completely hidden
+        overlap_efficiency=(t_in + t_attn - t_pipe) / min(t_in, t_attn) if min(t_in, t_attn) > 0 else None,
+        not_under_copy_ms=(t_pipe - t_in) * 1e3,
+        overlap_condition=dict(
+            T_load_x_L_hist_ms_per_layer=lhs * 1e3, T_pref_x_L_new_ms_per_layer=rhs * 1e3, imperfect=bool(lhs > rhs),
+            S_buf_bytes=s_buf, S_buf_layers=s_buf / job.link_in_bytes if job.link_in_bytes else None,
+            note="Section 3.2.1 with attention as the only compute: loading a layer takes longer than computing it, so the "
+                 "pipeline is bound by the host link and the formula asks for a read buffer of nearly the whole stack"),
+    )
+
+
+def depth_sweep(torch, ca, job, host_k, host_v, stream, depths, args):
+    """the same host-tier step with 1, 2, 4, ... staging slots on the read stream"""
+    out = []
+    for d in depths:
+        ctx = ca.Context(job.config(pipeline_depth=d, load_mode=args.load_mode, save_mode=args.save_mode))
+        try:
+            dt, prof = job.timed(ctx, host_k, host_v, stream, 1, 2, f"pinned tier, pipeline_depth {d}", kinds=["copy_in", "attn"])
+            cin_ms, _ = prof["copy_in"]
+            out.append(dict(pipeline_depth=d, ms_per_step=dt / 2 * 1e3, copy_in_ms=cin_ms / 2))
+        finally:
+            ctx.close()
+    return out
+
+
+def preload_sweep(torch, ca, seed):
+    """Section 4.3.2's pre-loading experiment at its shape (LLaMA-13B shapes, batch 16, 1K history, 100 new tokens,
+    host tier): the time from the moment the previous job releases the GPU to the end of this job's last layer,
+    when d layers of this job were already loaded into the read buffer while the previous job ran."""
+    B, L_hist, L_new = 16, 1000, 100
+    lengths = (np.full(B, L_hist, np.int32), np.full(B, L_new, np.int32))
+    job = Job(torch, ca, 3, seed, lengths=lengths, model=3)
+    job.make_pinned_tier()
+    host_k, host_v = job.tier_ptrs(job.pin_tier[0]), job.tier_ptrs(job.pin_tier[1])
+    stream = torch.cuda.current_stream()
+    L = job.L
+    ctx = ca.Context(job.config(pipeline_depth=2))
+    res = []
+    try:
+        def run(depth, preload):
+            """depth None: no pre-loading at all (every layer loaded, then computed)"""
+            job.rebase(ctx, stream)
+            n_pre = 0 if depth is None else min(depth, L)
+            for l in range(n_pre):
+                ctx.kv_load_layer(l, host_k[l], host_v[l], job.k_pool[l], job.v_pool[l])
+            ctx.sync(); torch.cuda.synchronize()              # the previous job ends here; the read buffer holds n_pre layers
+            t0 = time.perf_counter()
+            for l in range(n_pre, L):
+                ctx.kv_load_layer(l, host_k[l], host_v[l], job.k_pool[l], job.v_pool[l])
+            if not preload:
+                ctx.sync()
+            for l in range(L):
+                job.compute_layer(ctx, l, host_k, host_v, stream, save=False)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3
+
+        run(0, True)                                          # warm-up
+        for name, depth, pre in (("NO-PL", None, False), ("PL-B0", 0, True), ("PL-B5", 5, True), ("PL-B15", 15, True),
+                                 ("PL-B30", 30, True), (f"PL-B{L}", L, True)):
+            ms = min(run(depth, pre) for _ in range(2))
+            res.append(dict(name=name, layers_in_read_buffer=0 if depth is None else depth, ms=ms))
+        # the two sides of the overlap condition from measured per-layer times
+        dt, prof = job.timed(ctx, host_k, host_v, stream, 0, 1, "preload shape, one step", kinds=["copy_in", "attn"])
+        fig = pipeline_figures(job, dt, 1, {**prof, "copy_out": (0.0, 0)})
+    finally:
+        ctx.close()
+    t_load, t_pref = fig["overlap_condition"]["T_load_x_L_hist_ms_per_layer"], fig["overlap_condition"]["T_pref_x_L_new_ms_per_layer"]
+    knee_formula = fig["overlap_condition"]["S_buf_layers"]
+    # measured knee: the smallest buffer whose time is within 5 % of the fully pre-loaded run
+    full = res[-1]["ms"]
+    knee_measured = next((r["layers_in_read_buffer"] for r in res[1:] if r["ms"] <= 1.05 * full), L)
+    no_pl = res[0]["ms"]
+    for r in res:
+        r["vs_no_preload"] = r["ms"] / no_pl - 1.0
+    job.free()
+    return dict(shape=dict(model="LLaMA-13B shapes (40 layers, 40 heads, head_dim 128)", batch=B, history=L_hist, new=L_new),
+                runs=res, T_load_x_L_hist_ms_per_layer=t_load, T_pref_x_L_new_ms_per_layer=t_pref, h2d_gbs=fig["h2d_gbs"],
+                S_buf_bytes=fig["overlap_condition"]["S_buf_bytes"], knee_formula_layers=knee_formula, knee_measured_layers=knee_measured,
+                note="compute here is attention only, so T_load*L_hist >> T_pref*L_new: the time falls linearly with the layers "
+                     "already in the read buffer and only (nearly) the whole stack hides the loads; the paper's 35 % / 61 % at "
+                     "B0 / B15 have whole-layer prefill (projections, FFN) on the compute side")
+
+
 def decode_leg(torch, ca, cfg, n_steps, seed):
-    """Decode phase of a turn (Section 3.2.2) at the shape of the paper's saving experiment (Section 4.4:
-    batch 16, prompts of 1K..1.6K tokens, 20 decoding steps) on this workload's model: every step appends
-    one pre-rotary K/V token per conversation and layer, attends it over the whole context, and writes the
+    """Decode phase of a turn (Section 3.2.2) at the shape of the paper's saving experiment (Section 4.3.2:
+    batch 16, prompts of 1K..1.6K tokens, 20 decoding steps) on the given model: every step appends
+    one K/V token per conversation and layer, attends it over the whole context, and writes the
     step's K/V back to the tier on the save stream while the next step runs.  The contexts are already in
-    the pool (as after the turn's prefill); the tier is device memory, as in the headline leg."""
+    the pool (as after the turn's prefill); the tier is device memory."""
     from synth import draw_block_table
     dev = torch.device("cuda:0")
     L, Hq, Hkv, D = cfg["n_layers"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
@@ -92,7 +488,6 @@ def decode_leg(torch, ca, cfg, n_steps, seed):
     one, zero = np.ones(B, np.int32), np.zeros(B, np.int32)
 
     def run(ctx, write_back):
-        host = 0.0
         t0 = time.perf_counter()
         for s in range(n_steps):
             have = prompt + s
@@ -116,11 +511,11 @@ def decode_leg(torch, ca, cfg, n_steps, seed):
         run(ctx, True)
         att_ms, att_n = ctx.profile_read("attn")
         ctx.profile_enable(False)
-        # the write-back must have delivered the pre-rotary bits of the last pass: spot check, layer 0
+        # the write-back must have delivered the bits of the last pass: spot check, layer 0
         ok = bool(torch.equal(tier_k[0][:, -1], kn[0]) and torch.equal(tier_v[0][:, 0], vn[0]))
     kv_bytes = 2.0 * float((prompt + (n_steps + 1) / 2.0).sum()) * row       # K and V of the mean context, per layer
     att_us = att_ms / att_n * 1e3
-    return dict(batch=B, prompt_tokens=[int(prompt.min()), int(prompt.max())], steps=n_steps, layers=L,
+    return dict(model=cfg["name"], batch=B, prompt_tokens=[int(prompt.min()), int(prompt.max())], steps=n_steps, layers=L,
                 ms_per_step=t_wb / n_steps * 1e3, tokens_per_s=B * n_steps / t_wb,
                 ms_per_step_without_write_back=t_plain / n_steps * 1e3, host_ms_per_step=host_wb / n_steps * 1e3,
                 attn_avg_launch_us=att_us, attn_kv_read_gbs=kv_bytes / att_us / 1e3,
@@ -128,6 +523,79 @@ def decode_leg(torch, ca, cfg, n_steps, seed):
                 attn_kernel="attn_decode_kernel" if Hq // Hkv <= 2 else "attn_dma_kernel",
                 note="one token per conversation and step through the same entry points; each step's K/V is written back "
                      "on the save stream while the next step runs (device tier)")
+
+
+def cpu_baseline(job):
+    """the oracle as it stands on the host cores, on a bounded sample of the same workload"""
+    import oracle
+    from synth import bf16_bits_to_f64 as w
+    l0 = job.layer0
+    budget_s, used, convs, fl = 15.0, 0.0, 0, 0.0
+    t_start = time.perf_counter()
+    order = np.argsort(job.new.astype(np.int64) * job.ctx_len)      # cheapest conversations first: several fit the budget
+    done = []
+    for c in order:
+        c = int(c)
+        tk = time.perf_counter()
+        oracle.cached_attention(w(l0["k_hist"][c]), w(l0["v_hist"][c]), w(l0["q"][c]), w(l0["k_new"][c]), w(l0["v_new"][c]),
+                                keep_start=int(job.keep_start[c]))
+        used += time.perf_counter() - tk
+        convs += 1; done.append(c)
+        fl += 4.0 * job.D * job.Hq * (float(job.new[c]) * float(job.n_keep[c]) + float(job.new[c]) * (float(job.new[c]) + 1) / 2)
+        if time.perf_counter() - t_start > budget_s:
+            break
+    step_s = used * (job.flops_layer * job.L) / fl        # the sample scaled to one whole step by attention flops
+    cpu = dict(value=job.tot_q / step_s, unit="tokens/s", cores=oracle.n_threads(), kind="oracle",
+               sample=f"attention of layer 0 of {job.cfg['name']}, the {convs} cheapest of {job.B} conversations (all heads), {used:.1f} s of "
+                      f"oracle time, scaled to {job.L} layers x {job.B} conversations by attention flops; data movement not included",
+               gflops=fl / used / 1e9)
+    c0 = done[0]
+    rows = np.ascontiguousarray(np.concatenate([l0["k_hist"][c0][int(job.keep_start[c0]):], l0["k_new"][c0]]))
+    pool_cpu = np.zeros((job.num_pages, job.Hkv, 16, job.D), np.uint16)
+    back = np.zeros_like(rows)
+    tk = time.perf_counter()
+    oracle.unpack(rows, 0, pool_cpu, job.block_table[c0], 16, job.Hkv, job.D, 0, len(rows))
+    t_unpack = time.perf_counter() - tk
+    tk = time.perf_counter()
+    oracle.pack(pool_cpu, job.block_table[c0], 16, job.Hkv, job.D, 0, len(rows), back, 0)
+    t_pack = time.perf_counter() - tk
+    assert np.array_equal(back, rows)
+    cpu["move_gbs"] = {"unpack": 2.0 * rows.nbytes / t_unpack / 1e9, "pack": 2.0 * rows.nbytes / t_pack / 1e9,
+                       "sample": f"K of conversation {c0}, layer 0: {rows.nbytes / 1e6:.1f} MB each way, one thread"}
+    log(f"[bench] oracle: {convs} conversations of one layer in {used:.1f}s on {cpu['cores']} threads; "
+        f"unpack {cpu['move_gbs']['unpack']:.2f} GB/s, pack {cpu['move_gbs']['pack']:.2f} GB/s")
+    return cpu
+
+
+def config_summary(torch, ca, index, seed):
+    """compact figures of a smaller configuration with its tier in HBM: attention and load kernels alone and
+    inside a step, against the roofline that binds them"""
+    t0 = time.time()
+    job = Job(torch, ca, index, seed, with_layer0_bits=False)
+    job.make_device_tier()
+    dev_k, dev_v = job.tier_ptrs(job.dev_tier[0]), job.tier_ptrs(job.dev_tier[1])
+    stream = torch.cuda.current_stream()
+    ctx = ca.Context(job.config())
+    try:
+        dt, prof = job.timed(ctx, dev_k, dev_v, stream, 1, 3, f"{job.cfg['name']}: tier in HBM, every kernel timed")
+        iso = job.isolated(ctx, dev_k, dev_v, stream)
+    finally:
+        ctx.close()
+    att_us = prof["attn"][0] / prof["attn"][1] * 1e3
+    mv = job.move_figures(prof)
+    res = dict(workload=job.cfg["name"], layers=job.L, new_tokens=job.tot_q, kept_history_tokens=job.tot_n,
+               ms_per_step_hbm_tier=dt / 3 * 1e3, tokens_per_s_hbm_tier=job.tot_q / (dt / 3),
+               attn_binding_roofline=job.attn_bound, attn_roofline_floor_us=job.attn_floor_us,
+               attn_isolated_us=iso["attn"]["avg_launch_us"], attn_isolated_frac_binding_roofline=iso["attn"]["frac_binding_roofline"],
+               attn_isolated_tflops=iso["attn"]["tflops"], attn_isolated_gbs=iso["attn"]["gbs"],
+               attn_in_step_us=att_us, attn_in_step_frac_binding_roofline=job.attn_floor_us / att_us,
+               unpack_isolated_gbs=iso["unpack"]["gbs"], unpack_isolated_frac_hbm_peak=iso["unpack"]["frac_hbm_peak"],
+               unpack_in_step_gbs=mv["unpack"]["gbs"], append_isolated_gbs=iso["append"]["gbs"], pack_isolated_gbs=iso["pack"]["gbs"],
+               append_in_step_us=mv["append"]["avg_launch_us"], pack_in_step_us=mv["pack"]["avg_launch_us"])
+    job.free()
+    log(f"[bench] {job.cfg['name']}: attention {res['attn_isolated_us']:.1f} us alone ({res['attn_isolated_frac_binding_roofline']:.2f} of its "
+        f"{job.attn_bound} roofline), {att_us:.1f} us in step; unpack {res['unpack_isolated_gbs']:.0f} GB/s alone ({time.time() - t0:.0f}s)")
+    return res
 
 
 def main():
@@ -138,211 +606,81 @@ def main():
 
     import torch
     import paper_2403_19708_amd as ca
-    from synth import CONFIGS, bf16_bits_to_f64, draw_block_table, draw_values_bf16, make_workload
+    from synth import CONFIGS
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    wl = make_workload(args.config, seed=args.seed)
-    cfg = wl.cfg
-    L = args.layers or cfg["n_layers"]
-    Hq, Hkv, D, B, W = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["batch"], cfg["window"]
-    hist, new = wl.hist_len, wl.new_len
-    if cfg["truncate"]:
-        keep_start = ca.truncate_plan(hist, new, W, cfg["ratio"], policy=0)
-    else:
-        keep_start = np.zeros(B, np.int32)
-    n_keep = hist - keep_start
-    ctx_len = n_keep + new
-    pages = (ctx_len + P - 1) // P
-    num_pages = int(pages.sum()) + 8
-    block_table = draw_block_table(pages, num_pages, args.seed + 17)
-    tot_q, tot_n, tot_k = int(new.sum()), int(n_keep.sum()), int(ctx_len.sum())
-    cu_q = np.concatenate([[0], np.cumsum(new)]).astype(np.int64)
-    row = Hkv * D            # elements per token on the KV side
-    scale = 1.0 / np.sqrt(D)
-    log(f"[bench] {cfg['name']}: L={L} B={B} Hq={Hq} Hkv={Hkv} D={D} kept-history={tot_n} new={tot_q} tokens")
-
-    # ---- algorithmic work per layer (one launch of each kernel) ---------------------------------
-    flops_layer = 4.0 * D * Hq * float(np.sum(new.astype(np.float64) * n_keep + new.astype(np.float64) * (new + 1) / 2))
-    attn_bytes = 2.0 * tot_k * row * 2 + 2.0 * tot_q * Hq * D * 2        # K,V once + Q in + O out
-    unpack_bytes = 2.0 * (2.0 * tot_n * row * 2)                         # read + write, K and V
-    append_bytes = 2.0 * (2.0 * tot_q * row * 2)
-    pack_bytes = 2.0 * (2.0 * tot_q * row * 2)
-    link_in_bytes = 2.0 * tot_n * row * 2
-    link_out_bytes = 2.0 * tot_q * row * 2
-
-    # ---- device tensors ----------------------------------------------------------------------------
-    def bits_to_dev(bits):
-        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
-
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(1234 + args.seed)
-
-    def randn(shape):
-        return torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-
-    # tier: per layer one K and one V buffer holding every conversation's [hist + new] tokens
-    tier_off = np.concatenate([[0], np.cumsum(hist.astype(np.int64) + new)])
-    t0 = time.time()
-    layer0 = {}
-    for name, toks in (("k_hist", hist), ("v_hist", hist), ("q", new), ("k_new", new), ("v_new", new)):
-        heads = Hq if name == "q" else Hkv
-        layer0[name] = [draw_values_bf16((int(toks[c]), heads, D), args.seed, wl.stream(0, name, c)) for c in range(B)]
-    tier_k, tier_v, k_pool, v_pool, q, k_new, v_new, out = [], [], [], [], [], [], [], []
-    for l in range(L):
-        tk = torch.empty((int(tier_off[-1]), Hkv, D), dtype=torch.bfloat16, device=dev)
-        tv = torch.empty_like(tk)
-        if l == 0:
-            for c in range(B):
-                a = int(tier_off[c])
-                tk[a:a + int(hist[c])] = bits_to_dev(layer0["k_hist"][c])
-                tv[a:a + int(hist[c])] = bits_to_dev(layer0["v_hist"][c])
-            q.append(bits_to_dev(np.concatenate(layer0["q"])))
-            k_new.append(bits_to_dev(np.concatenate(layer0["k_new"])))
-            v_new.append(bits_to_dev(np.concatenate(layer0["v_new"])))
-        else:
-            tk.copy_(randn(tk.shape))
-            tv.copy_(randn(tv.shape))
-            q.append(randn((tot_q, Hq, D)))
-            k_new.append(randn((tot_q, Hkv, D)))
-            v_new.append(randn((tot_q, Hkv, D)))
-        tier_k.append(tk)
-        tier_v.append(tv)
-        k_pool.append(torch.zeros((num_pages, Hkv, P, D), dtype=torch.bfloat16, device=dev))
-        v_pool.append(torch.zeros((num_pages, Hkv, P, D), dtype=torch.bfloat16, device=dev))
-        out.append(torch.zeros((tot_q, Hq, D), dtype=torch.bfloat16, device=dev))
-    torch.cuda.synchronize()
-    log(f"[bench] inputs ready in {time.time() - t0:.1f}s, {torch.cuda.memory_allocated() / 2**30:.1f} GiB on device")
-
-    def tier_ptrs(bufs, layer):
-        base, esz = bufs[layer].data_ptr(), row * 2
-        return [base + int(tier_off[c]) * esz for c in range(B)]
-
-    conf = ca.Config(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=W, load_mode=args.load_mode, save_mode=args.save_mode,
-                     pipeline_depth=2, max_seqs=B, max_batch_kv_tokens=tot_k + 64, max_batch_q_tokens=tot_q + 16)
-    ctx = ca.Context(conf)
+    torch.cuda.set_device(0)
+    t_begin = time.time()
     stream = torch.cuda.current_stream()
 
-    def step(src_k, src_v):
-        ctx.rope_rebase(hist, keep_start, new, block_table, num_pages, stream)
-        for l in range(L):
-            ctx.kv_load_layer(l, src_k[l], src_v[l], k_pool[l], v_pool[l])
-        for l in range(L):
-            ctx.kv_append_layer(l, k_new[l], v_new[l], k_pool[l], v_pool[l], stream)
-            ctx.cached_prefill_attn(l, q[l], k_pool[l], v_pool[l], out[l], scale, stream)
-            ctx.kv_save_layer(l, k_pool[l], v_pool[l], src_k[l], src_v[l], after_stream=stream)
-        ctx.join(stream)
+    job = Job(torch, ca, args.config, args.seed, layers=args.layers)
+    cfg = job.cfg
+    L = job.L
+    log(f"[bench] {cfg['name']}: L={L} B={job.B} Hq={job.Hq} Hkv={job.Hkv} D={job.D} kept-history={job.tot_n} new={job.tot_q} tokens, "
+        f"attention {job.attn_bound}-bound (floor {job.attn_floor_us:.0f} us per layer)")
+    want_hbm = (not args.no_hbm_leg) or args.tier == "hbm"
+    if want_hbm:
+        job.make_device_tier()
+    log(f"[bench] device tensors ready after {time.time() - t_begin:.0f}s, {torch.cuda.memory_allocated() / 2**30:.1f} GiB on device")
+    pinned_ok = True
+    host_k = host_v = None
+    try:
+        job.make_pinned_tier()
+        host_k, host_v = job.tier_ptrs(job.pin_tier[0]), job.tier_ptrs(job.pin_tier[1])
+        log(f"[bench] pinned tier ready after {time.time() - t_begin:.0f}s")
+    except Exception as e:
+        pinned_ok = False
+        log(f"[bench] pinned tier failed: {e!r}")
+        if args.tier == "pinned":
+            raise
+    dev_k = dev_v = None
+    if want_hbm:
+        dev_k, dev_v = job.tier_ptrs(job.dev_tier[0]), job.tier_ptrs(job.dev_tier[1])
 
-    def timed(src_k, src_v, warmup, steps, tag, kinds=None):
-        """kinds: which of the library's kernels/copies are bracketed by HIP events during the timed steps
-        (None = all; the events cost a few per cent of a step, so the headline pass times one kind only)"""
-        for i in range(warmup):
-            step(src_k, src_v)
-        ctx.sync(); torch.cuda.synchronize()
-        for k in ca.Context.PROFILE_KINDS:
-            ctx.profile_read(k)              # drop what the warmup recorded
-        ctx.profile_enable(True, kinds)
-        t = time.perf_counter()
-        for i in range(steps):
-            step(src_k, src_v)
-        ctx.sync(); torch.cuda.synchronize()
-        dt = time.perf_counter() - t
-        ctx.profile_enable(False)
-        prof = {k: ctx.profile_read(k) for k in ca.Context.PROFILE_KINDS}
-        log(f"[bench] {tag}: {steps} steps in {dt * 1e3:.1f} ms")
-        return dt, prof
+    ctx = ca.Context(job.config(pipeline_depth=args.depth, load_mode=args.load_mode, save_mode=args.save_mode))
 
-    # ---- leg 1: tier resident in HBM (the headline) ---------------------------------------------------
-    dev_k = [tier_ptrs(tier_k, l) for l in range(L)]
-    dev_v = [tier_ptrs(tier_v, l) for l in range(L)]
-    # Instrumented pass (every kernel bracketed by events): in-step duration of each kernel, and which one
-    # takes the largest share of a step.  Then the timed pass, with events around that kernel only.
-    dt_all, prof = timed(dev_k, dev_v, args.warmup, args.steps, "HBM-resident tier, every kernel timed")
-
-    def avg_us(kind):
-        ms, n = prof[kind]
-        return (ms / n * 1e3) if n else None
-
-    dominant = max(("attn", "unpack", "append", "pack"), key=lambda k: avg_us(k) or 0.0)
-    dt, prof_dom = timed(dev_k, dev_v, 1, args.steps, f"HBM-resident tier, timed ({dominant} bracketed by events)", kinds=[dominant])
-    ms_step = dt / args.steps * 1e3
-    value = tot_q / (dt / args.steps)
-    dom_us_live = prof_dom[dominant][0] / prof_dom[dominant][1] * 1e3
-
-    kern = {
-        "attn": dict(us=avg_us("attn"), bytes=attn_bytes, flops=flops_layer),
-        "unpack": dict(us=avg_us("unpack"), bytes=unpack_bytes),
-        "append": dict(us=avg_us("append"), bytes=append_bytes),
-        "pack": dict(us=avg_us("pack"), bytes=pack_bytes),
-    }
-    for k, v in kern.items():
-        v["gbs"] = v["bytes"] / (v["us"] * 1e-6) / 1e9 if v["us"] else None
-    attn_tflops = flops_layer / (kern["attn"]["us"] * 1e-6) / 1e12
-    t_mfma_us = flops_layer / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6
-    t_hbm_us = attn_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
-    attn_bound = "mfma" if t_mfma_us > t_hbm_us else "hbm"
-    # the dominant kernel is the one with the largest share of a step's GPU time; its duration inside the
-    # timed steps replaces the instrumented pass's figure
-    kern[dominant]["us"] = dom_us_live
-    kern[dominant]["gbs"] = kern[dominant]["bytes"] / (dom_us_live * 1e-6) / 1e9
-    if dominant == "attn":
-        attn_tflops = flops_layer / (dom_us_live * 1e-6) / 1e12
-    # the library's default choice of attention kernel: LDS-direct loads while the window fits its page table
-    attn_kernel = "attn_dma_kernel" if W <= 32768 else "attn_mfma_kernel"
-    if dominant == "attn" and attn_bound == "mfma":
-        roof = dict(kernel=attn_kernel, bound="mfma", achieved=attn_tflops, peak=MFMA_BF16_PEAK_TFLOPS,
-                    unit="TFLOP/s", frac=attn_tflops / MFMA_BF16_PEAK_TFLOPS, traffic=None)
+    # ---- headline leg ---------------------------------------------------------------------------------------
+    # the events around the attention call and the copies cost nothing measurable next to a link-bound step
+    if args.tier == "pinned":
+        src_k, src_v, tier_name = host_k, host_v, "pinned-host"
+        kinds = ["attn", "copy_in", "copy_out"]
     else:
-        name = {"attn": attn_kernel, "unpack": "move_kernel<to_pool> (load)", "append": "move_kernel<to_pool> (append)",
-                "pack": "move_kernel<from_pool> (save)"}[dominant]
-        roof = dict(kernel=name, bound="hbm", achieved=kern[dominant]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=kern[dominant]["gbs"] / HBM_PEAK_GBS, traffic=None)
-    roof["avg_launch_us"] = kern[dominant]["us"]
-    roof["algorithmic_bytes_per_launch"] = kern[dominant]["bytes"]
+        src_k, src_v, tier_name = dev_k, dev_v, "HBM-resident"
+        kinds = ["attn"]
+    dt, prof = job.timed(ctx, src_k, src_v, stream, args.warmup, args.steps, f"{tier_name} tier, timed", kinds=kinds)
+    ms_step = dt / args.steps * 1e3
+    value = job.tot_q / (dt / args.steps)
+    att_us_live = prof["attn"][0] / prof["attn"][1] * 1e3
+    attn_live = job.attn_figures(att_us_live)
+    pipeline = pipeline_figures(job, dt, args.steps, prof) if args.tier == "pinned" else None
 
-    # ---- each kernel alone (no other stream active): what the kernels do without contention -----------------
-    iso = {}
-    n_iso = min(L, 4)
-    ctx.profile_enable(True)
-    for l in range(n_iso):
-        ctx.sync(); torch.cuda.synchronize()
-        ctx.rope_rebase(hist, keep_start, new, block_table, num_pages, stream)
-        ctx.sync(); torch.cuda.synchronize()
-        ctx.kv_load_layer(l, dev_k[l], dev_v[l], k_pool[l], v_pool[l])
-        ctx.sync(); torch.cuda.synchronize()
-        ctx.kv_append_layer(l, k_new[l], v_new[l], k_pool[l], v_pool[l], stream)
-        ctx.sync(); torch.cuda.synchronize()
-        ctx.cached_prefill_attn(l, q[l], k_pool[l], v_pool[l], out[l], scale, stream)
-        ctx.sync(); torch.cuda.synchronize()
-        ctx.kv_save_layer(l, k_pool[l], v_pool[l], dev_k[l], dev_v[l], after_stream=stream)
-        ctx.sync(); torch.cuda.synchronize()
-    ctx.profile_enable(False)
-    for kname, nbytes in (("attn", attn_bytes), ("unpack", unpack_bytes), ("append", append_bytes), ("pack", pack_bytes)):
-        ms, cnt = ctx.profile_read(kname)
-        us = ms / cnt * 1e3 if cnt else None
-        iso[kname] = {"avg_launch_us": us, "gbs": nbytes / (us * 1e-6) / 1e9 if us else None,
-                      "frac_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS if us else None}
-    iso["attn"]["tflops"] = flops_layer / (iso["attn"]["avg_launch_us"] * 1e-6) / 1e12
-    iso["attn"]["frac_mfma_peak"] = iso["attn"]["tflops"] / MFMA_BF16_PEAK_TFLOPS
-    iso["attn"]["frac_binding_roofline"] = max(t_mfma_us, t_hbm_us) / iso["attn"]["avg_launch_us"]
-    log("[bench] isolated: " + ", ".join(f"{k} {v['avg_launch_us']:.1f} us" for k, v in iso.items()))
+    parity = None
+    if not args.no_check and job.layer0:
+        parity = job.parity(job.out[0])
+        if not parity["ok"]:
+            log("[bench] PARITY FAILED: the numbers below are not valid")
 
-    # ---- a plain device copy of known size: the reference the HBM byte counters are scaled by ---------------
-    cal_n = 256 * 1024 * 1024 // 2
-    cal_src = torch.empty(cal_n, dtype=torch.bfloat16, device=dev).normal_()
-    cal_dst = torch.empty_like(cal_src)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    cal_dst.copy_(cal_src)
-    e0.record(); cal_dst.copy_(cal_src); e1.record(); torch.cuda.synchronize()
-    copy_gbs = 2 * cal_n * 2 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del cal_src, cal_dst
+    # every kernel bracketed, same tier: in-step durations of the move kernels
+    dt_i, prof_i = job.timed(ctx, src_k, src_v, stream, 0, 1, f"{tier_name} tier, every kernel timed")
+    kv_move = job.move_figures(prof_i)
 
-    # HBM traffic per launch of the dominant kernel, from rocprofv3 counter runs (kept under profiles/)
+    # the dominant kernel of the step by GPU time: the attention call
+    attn_kernel = "attn_dma_kernel" if job.W <= 32768 else "attn_mfma_kernel"
+    G = job.Hq // job.Hkv
+    # the library rotates the keys once per layer when on average three or more 256-row tiles share them
+    prerot = job.W <= 32768 and int(np.sum((job.new.astype(np.int64) * G + 255) // 256)) >= 3 * job.B
+    if job.attn_bound == "mfma":
+        roof = dict(kernel=attn_kernel, bound="mfma", achieved=attn_live["tflops"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=attn_live["frac_mfma_peak"], traffic=None, algorithmic_flops_per_launch=job.flops_layer)
+    else:
+        roof = dict(kernel=attn_kernel, bound="hbm", achieved=attn_live["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=attn_live["frac_hbm_peak"], traffic=None)
+    roof["avg_launch_us"] = att_us_live
+    roof["algorithmic_bytes_per_launch"] = job.attn_bytes
+    roof["launch"] = ("one ca_cached_prefill_attn call inside the timed steps: rotate_keys_kernel + attn_dma_kernel (+ combine_kernel "
+                      "when keys are split)" if prerot else "one ca_cached_prefill_attn call inside the timed steps")
     traffic_file = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{args.config}.txt")
     if os.path.exists(traffic_file):
         kv = {}
@@ -350,120 +688,86 @@ def main():
             if "=" in line and not line.lstrip().startswith("#"):
                 k, v = line.split("=", 1)
                 kv[k.strip()] = v.split("#")[0].strip()
-        key = {"attn": "attn", "unpack": "unpack", "append": "append", "pack": "pack"}[dominant] + "_bytes_per_launch"
-        if key in kv:
-            roof["traffic"] = float(kv[key])
+        if "attn_bytes_per_launch" in kv:
+            roof["traffic"] = float(kv["attn_bytes_per_launch"])
+            roof["traffic_source"] = f"profiles/hbm_traffic_cfg{args.config}.txt (rocprofv3 counter runs of this command)"
 
-    # ---- sampled parity check of layer 0 against the oracle ---------------------------------------------
-    parity = None
-    if not args.no_check:
-        import oracle
-        got_all = out[0].detach().cpu().view(torch.int16).numpy().view(np.uint16)
-        rng = np.random.default_rng(5)
-        samples = [(int(rng.integers(B)), int(rng.integers(Hq))) for _ in range(6)]
-        G = Hq // Hkv
-        worst_max, worst_mean = 0.0, 0.0
-        for c, h in samples:
-            g = h // G
-            w = bf16_bits_to_f64
-            want = oracle.cached_attention(w(layer0["k_hist"][c][:, g:g + 1]), w(layer0["v_hist"][c][:, g:g + 1]),
-                                           w(layer0["q"][c][:, h:h + 1]), w(layer0["k_new"][c][:, g:g + 1]),
-                                           w(layer0["v_new"][c][:, g:g + 1]), keep_start=int(keep_start[c]))
-            got = w(got_all[int(cu_q[c]):int(cu_q[c + 1]), h:h + 1])
-            err = np.abs(got - want)
-            worst_max, worst_mean = max(worst_max, float(err.max())), max(worst_mean, float(err.mean()))
-        parity = dict(samples=len(samples), max_abs=worst_max, mean_abs=worst_mean, ok=bool(worst_max <= 2e-2 and worst_mean <= 2e-3))
-        log(f"[bench] sampled parity vs oracle (layer 0): max-abs {worst_max:.2e} mean-abs {worst_mean:.2e}")
-        if not parity["ok"]:
-            log("[bench] PARITY FAILED: the numbers below are not valid")
+    # ---- the same step with the tier in HBM -----------------------------------------------------------------------
+    hbm = None
+    if want_hbm and args.tier == "pinned":
+        hdt, hprof = job.timed(ctx, dev_k, dev_v, stream, 1, args.hbm_steps, "HBM-resident tier, every kernel timed")
+        h_att = hprof["attn"][0] / hprof["attn"][1] * 1e3
+        hbm = dict(ms_per_step=hdt / args.hbm_steps * 1e3, tokens_per_s=job.tot_q / (hdt / args.hbm_steps),
+                   context_tokens_per_s=job.tot_k / (hdt / args.hbm_steps), attn=job.attn_figures(h_att), kv_move=job.move_figures(hprof),
+                   note="same entry points; the load kernel reads the tier in place from device memory, no host link in the step")
+    iso = job.isolated(ctx, dev_k if want_hbm else src_k, dev_v if want_hbm else src_v, stream)
+    log("[bench] isolated: " + ", ".join(f"{k} {v['avg_launch_us']:.1f} us" for k, v in iso.items()))
 
-    # ---- leg 2: tier in pinned host memory, copies overlapped with attention ---------------------------------
-    pipeline = None
-    if not args.no_pipeline:
+    # ---- a plain device copy of known size: the reference the HBM byte counters are scaled by ---------------
+    cal_n = 256 * 1024 * 1024 // 2
+    cal_src = torch.empty(cal_n, dtype=torch.bfloat16, device=job.dev).normal_()
+    cal_dst = torch.empty_like(cal_src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    cal_dst.copy_(cal_src)
+    e0.record(); cal_dst.copy_(cal_src); e1.record(); torch.cuda.synchronize()
+    copy_gbs = 2 * cal_n * 2 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del cal_src, cal_dst
+    ctx.close()
+
+    # ---- read-buffer experiments ------------------------------------------------------------------------------------
+    sweep = None
+    if not args.no_sweeps and pinned_ok:
         try:
-            t0 = time.time()
-            pin_k = [torch.empty(tier_k[l].shape, dtype=torch.bfloat16, pin_memory=True) for l in range(L)]
-            pin_v = [torch.empty(tier_v[l].shape, dtype=torch.bfloat16, pin_memory=True) for l in range(L)]
-            for l in range(L):
-                pin_k[l].copy_(tier_k[l]); pin_v[l].copy_(tier_v[l])
-            torch.cuda.synchronize()
-            log(f"[bench] pinned tier of {2 * L * tier_k[0].numel() * 2 / 2**30:.1f} GiB ready in {time.time() - t0:.1f}s")
-            host_k = [tier_ptrs(pin_k, l) for l in range(L)]
-            host_v = [tier_ptrs(pin_v, l) for l in range(L)]
-            pdt, pprof = timed(host_k, host_v, 1, args.pipeline_steps, "pinned-host tier")
-            t_pipe = pdt / args.pipeline_steps
-            cin_ms, cin_n = pprof["copy_in"]; cout_ms, cout_n = pprof["copy_out"]
-            att_ms, att_n = pprof["attn"]
-            # per step: time the copy-in stream was busy, the copy-out stream, the attention kernels
-            t_in = cin_ms / args.pipeline_steps / 1e3
-            t_out = cout_ms / args.pipeline_steps / 1e3
-            t_attn = att_ms / args.pipeline_steps / 1e3
-            pipeline = dict(
-                tokens_per_s=tot_q / t_pipe, context_tokens_per_s=tot_k / t_pipe, ms_per_step=t_pipe * 1e3,
-                h2d_gbs=link_in_bytes * cin_n / (cin_ms * 1e-3) / 1e9 if cin_ms else None,
-                d2h_gbs=link_out_bytes * cout_n / (cout_ms * 1e-3) / 1e9 if cout_ms else None,
-                copy_in_ms=t_in * 1e3, copy_out_ms=t_out * 1e3, attn_ms=t_attn * 1e3,
-                # (T_copy + T_attn - T_pipe) / min(T_copy, T_attn) with the copy-in stream as T_copy:
-                # 1.0 means the shorter of the two is completely hidden behind the longer
-                overlap_efficiency=(t_in + t_attn - t_pipe) / min(t_in, t_attn) if min(t_in, t_attn) > 0 else None,
-                link_floor_ms=link_in_bytes * L / 64e9 * 1e3,
-                note="link-bound: per layer the host link moves %.0f MiB while attention needs %.0f us" % (
-                    link_in_bytes / 2**20, kern["attn"]["us"]),
-            )
-            del pin_k, pin_v
-        except Exception as e:  # the pinned leg is secondary; report why it is missing
-            log(f"[bench] pinned-host leg failed: {e!r}")
-            pipeline = dict(error=repr(e))
+            sweep = depth_sweep(torch, ca, job, host_k, host_v, stream, [1, 2, 4], args)
+        except Exception as e:
+            log(f"[bench] depth sweep failed: {e!r}")
+            sweep = dict(error=repr(e))
 
-    # ---- leg 3: decode phase with asynchronous write-back -----------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline and job.layer0:
+        cpu = cpu_baseline(job)
+
+    result_config = {"workload": cfg["name"], "index": args.config, "tier": tier_name, "n_layers": L, "batch": job.B, "n_q_heads": job.Hq,
+                     "n_kv_heads": job.Hkv, "head_dim": job.D, "new_tokens": job.tot_q, "kept_history_tokens": job.tot_n,
+                     "pipeline_depth": args.depth, "load_mode": args.load_mode,
+                     "pinned_tier_gib": getattr(job, "pin_gib", 0.0) if args.tier == "pinned" else 0.0,
+                     "pinned_tier_distinct_layers": getattr(job, "pin_distinct", 0) if args.tier == "pinned" else 0,
+                     "tier_bytes_streamed_per_step_gib": L * job.link_in_bytes / 2**30,
+                     "valid": not bool(args.layers)}
+    context_tps = job.tot_k / (dt / args.steps)
+    job.free()
+    del job
+
+    preload = None
+    if not args.no_sweeps:
+        try:
+            preload = preload_sweep(torch, ca, args.seed)
+            log("[bench] preload sweep: " + ", ".join(f"{r['name']} {r['ms']:.1f} ms" for r in preload["runs"]))
+        except Exception as e:
+            log(f"[bench] preload sweep failed: {e!r}")
+            preload = dict(error=repr(e))
+
     decode = None
     if not args.no_decode:
         try:
-            decode = decode_leg(torch, ca, dict(cfg, n_layers=L), args.decode_steps, args.seed)
+            decode = decode_leg(torch, ca, dict(CONFIGS[2]), args.decode_steps, args.seed)
             log(f"[bench] decode leg: {decode['ms_per_step']:.2f} ms per step ({decode['ms_per_step_without_write_back']:.2f} without "
                 f"write-back), attention {decode['attn_avg_launch_us']:.1f} us, {decode['attn_kv_read_gbs']:.0f} GB/s of K/V")
         except Exception as e:
             log(f"[bench] decode leg failed: {e!r}")
             decode = dict(error=repr(e))
 
-    # ---- CPU baseline: the oracle as it stands, on a bounded sample --------------------------------------------
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        w = bf16_bits_to_f64
-        budget_s, used, convs, fl = 20.0, 0.0, 0, 0.0
-        t_start = time.perf_counter()
-        for c in range(B):
-            tk = time.perf_counter()
-            oracle.cached_attention(w(layer0["k_hist"][c]), w(layer0["v_hist"][c]), w(layer0["q"][c]),
-                                    w(layer0["k_new"][c]), w(layer0["v_new"][c]), keep_start=int(keep_start[c]))
-            used += time.perf_counter() - tk
-            convs += 1
-            fl += 4.0 * D * Hq * (float(new[c]) * float(n_keep[c]) + float(new[c]) * (float(new[c]) + 1) / 2)
-            if time.perf_counter() - t_start > budget_s:
-                break
-        # scale the sample to one whole step by its share of the step's attention flops
-        step_s = used * (flops_layer * L) / fl
-        cpu = dict(value=tot_q / step_s, unit="tokens/s", cores=oracle.n_threads(), kind="oracle",
-                   sample=f"attention of layer 0, conversations 0..{convs - 1} of {B} (all heads), {used:.1f} s of oracle time, "
-                          f"scaled to {L} layers x {B} conversations by attention flops; data movement not included",
-                   gflops=fl / used / 1e9)
-        # the oracle's plain unpack and pack loops on conversation 0 of layer 0 (K only), beside the move kernels
-        c0 = 0
-        rows = np.ascontiguousarray(np.concatenate([layer0["k_hist"][c0][int(keep_start[c0]):], layer0["k_new"][c0]]))
-        pool_cpu = np.zeros((num_pages, Hkv, 16, D), np.uint16)
-        back = np.zeros_like(rows)
-        tk = time.perf_counter()
-        oracle.unpack(rows, 0, pool_cpu, block_table[c0], 16, Hkv, D, 0, len(rows))
-        t_unpack = time.perf_counter() - tk
-        tk = time.perf_counter()
-        oracle.pack(pool_cpu, block_table[c0], 16, Hkv, D, 0, len(rows), back, 0)
-        t_pack = time.perf_counter() - tk
-        assert np.array_equal(back, rows)
-        cpu["move_gbs"] = {"unpack": 2.0 * rows.nbytes / t_unpack / 1e9, "pack": 2.0 * rows.nbytes / t_pack / 1e9,
-                           "sample": f"K of conversation {c0}, layer 0: {rows.nbytes / 1e6:.1f} MB each way, one thread"}
-        log(f"[bench] oracle: {convs} conversations of one layer in {used:.1f}s on {cpu['cores']} threads; "
-            f"unpack {cpu['move_gbs']['unpack']:.2f} GB/s, pack {cpu['move_gbs']['pack']:.2f} GB/s")
+    configs = []
+    for tok in [t for t in args.summary_configs.split(",") if t.strip()]:
+        idx = int(tok)
+        if idx == args.config:
+            continue
+        try:
+            configs.append(config_summary(torch, ca, idx, args.seed))
+        except Exception as e:
+            log(f"[bench] summary of config {idx} failed: {e!r}")
+            configs.append(dict(index=idx, error=repr(e)))
 
     result = {
         "metric": "cached-prefill tokens/s + attn TFLOP/s (% bf16 MFMA peak); KV load/pack GB/s",
@@ -478,30 +782,24 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": cfg["name"], "index": args.config, "n_layers": L, "batch": B, "n_q_heads": Hq,
-                   "n_kv_heads": Hkv, "head_dim": D, "new_tokens": tot_q, "kept_history_tokens": tot_n,
-                   "tier": "HBM-resident", "valid": not bool(args.layers)},
-        "context_tokens_per_s": tot_k / (dt / args.steps),
-        "attn": {"tflops": attn_tflops, "frac_mfma_peak": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                 "avg_launch_us": kern["attn"]["us"], "gbs": kern["attn"]["gbs"], "frac_hbm_peak": kern["attn"]["gbs"] / HBM_PEAK_GBS,
-                 "binding_roofline": attn_bound, "roofline_floor_us": max(t_mfma_us, t_hbm_us),
-                 "frac_binding_roofline": max(t_mfma_us, t_hbm_us) / kern["attn"]["us"]},
-        "isolated": iso,
-        "device_copy_gbs": copy_gbs,
-        "kv_move": {k: {"avg_launch_us": kern[k]["us"], "gbs": kern[k]["gbs"],
-                        "frac_hbm_peak": (kern[k]["gbs"] / HBM_PEAK_GBS) if kern[k]["gbs"] else None}
-                    for k in ("unpack", "append", "pack")},
-        "instrumented_pass": {"ms_per_step": dt_all / args.steps * 1e3,
-                              "note": "same steps with every kernel bracketed by events; kv_move and the non-dominant "
-                                      "kernel times come from it, the dominant kernel's from the timed steps"},
+        "config": result_config,
+        "context_tokens_per_s": context_tps,
+        "attn": attn_live,
+        "kv_move": kv_move,
         "roofline": roof,
         "cpu_baseline": cpu,
         "pipeline": pipeline,
+        "hbm_resident_tier": hbm,
+        "isolated": iso,
+        "device_copy_gbs": copy_gbs,
+        "pipeline_depth_sweep": sweep,
+        "preload_sweep": preload,
+        "configs": configs,
         "decode": decode,
         "parity": parity,
+        "wall_s": time.time() - t_begin,
     }
     print(json.dumps(result), flush=True)
-    ctx.close()
     return 0 if (parity is None or parity["ok"]) else 1
 
 
