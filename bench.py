@@ -236,7 +236,13 @@ class Job:
     def rebase(self, ctx, stream):
         ctx.rope_rebase(self.hist, self.keep_start, self.new, self.block_table, self.num_pages, stream)
 
+    fused_save = True      # the new turn is appended and saved by one call that reads it once (False: the two calls)
+
     def compute_layer(self, ctx, l, src_k, src_v, stream, save=True):
+        if save and self.fused_save:
+            ctx.kv_append_save_layer(l, self.k_new[l], self.v_new[l], self.k_pool[l], self.v_pool[l], src_k[l], src_v[l], stream)
+            ctx.cached_prefill_attn(l, self.q[l], self.k_pool[l], self.v_pool[l], self.out[l], self.scale, stream)
+            return
         ctx.kv_append_layer(l, self.k_new[l], self.v_new[l], self.k_pool[l], self.v_pool[l], stream)
         ctx.cached_prefill_attn(l, self.q[l], self.k_pool[l], self.v_pool[l], self.out[l], self.scale, stream)
         if save:
@@ -288,13 +294,28 @@ class Job:
             sync()
         ctx.profile_enable(False)
         iso = {}
+        sep = {k: ctx.profile_read(k) for k in ("append", "pack")}
+        ctx.profile_enable(True, ["append"])
+        for l in range(n_iso):
+            sync(); ctx.kv_append_save_layer(l, self.k_new[l], self.v_new[l], self.k_pool[l], self.v_pool[l], src_k[l], src_v[l], stream)
+            sync()
+        ctx.profile_enable(False)
+        f_ms, f_n = ctx.profile_read("append")
+        ctx.profile_read("copy_out")
+        fused_us = f_ms / f_n * 1e3 if f_n else None
         for kname, nbytes in (("attn", self.attn_bytes), ("unpack", self.unpack_bytes), ("append", self.append_bytes), ("pack", self.pack_bytes)):
-            ms, cnt = ctx.profile_read(kname)
+            ms, cnt = sep[kname] if kname in sep else ctx.profile_read(kname)
             us = ms / cnt * 1e3 if cnt else None
             iso[kname] = {"avg_launch_us": us, "gbs": nbytes / (us * 1e-6) / 1e9 if us else None,
                           "frac_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS if us else None}
         for k in ("copy_in", "copy_out"):
             ctx.profile_read(k)
+        if fused_us:
+            nb = self.append_bytes * 1.5
+            iso["append_save_fused"] = {"avg_launch_us": fused_us, "gbs": nb / (fused_us * 1e-6) / 1e9,
+                                        "frac_hbm_peak": nb / (fused_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                                        "vs_two_calls": fused_us / (iso["append"]["avg_launch_us"] + iso["pack"]["avg_launch_us"]) - 1.0
+                                        if iso["append"]["avg_launch_us"] and iso["pack"]["avg_launch_us"] else None}
         a = iso["attn"]
         a["tflops"] = self.flops_layer / (a["avg_launch_us"] * 1e-6) / 1e12
         a["frac_mfma_peak"] = a["tflops"] / MFMA_BF16_PEAK_TFLOPS
@@ -310,9 +331,11 @@ class Job:
                 "frac_hbm_peak": gbs / HBM_PEAK_GBS, "binding_roofline": self.attn_bound, "roofline_floor_us": self.attn_floor_us,
                 "frac_binding_roofline": self.attn_floor_us / us}
 
-    def move_figures(self, prof):
+    def move_figures(self, prof, fused_device_tier=False):
+        """fused_device_tier: the append figure is the one-pass append + save kernel (read N, write 2N bytes)"""
         out = {}
-        for k, nbytes in (("unpack", self.unpack_bytes), ("append", self.append_bytes), ("pack", self.pack_bytes)):
+        app = self.append_bytes * 1.5 if fused_device_tier else self.append_bytes
+        for k, nbytes in (("unpack", self.unpack_bytes), ("append", app), ("pack", self.pack_bytes)):
             ms, n = prof[k]
             us = ms / n * 1e3 if n else None
             out[k] = {"avg_launch_us": us, "gbs": nbytes / (us * 1e-6) / 1e9 if us else None,
@@ -582,7 +605,7 @@ def config_summary(torch, ca, index, seed):
     finally:
         ctx.close()
     att_us = prof["attn"][0] / prof["attn"][1] * 1e3
-    mv = job.move_figures(prof)
+    mv = job.move_figures(prof, fused_device_tier=True)
     res = dict(workload=job.cfg["name"], layers=job.L, new_tokens=job.tot_q, kept_history_tokens=job.tot_n,
                ms_per_step_hbm_tier=dt / 3 * 1e3, tokens_per_s_hbm_tier=job.tot_q / (dt / 3),
                attn_binding_roofline=job.attn_bound, attn_roofline_floor_us=job.attn_floor_us,
@@ -697,8 +720,18 @@ def main():
     if want_hbm and args.tier == "pinned":
         hdt, hprof = job.timed(ctx, dev_k, dev_v, stream, 1, args.hbm_steps, "HBM-resident tier, every kernel timed")
         h_att = hprof["attn"][0] / hprof["attn"][1] * 1e3
+        job.fused_save = False
+        sdt, sprof = job.timed(ctx, dev_k, dev_v, stream, 0, 1, "HBM-resident tier, append and save as two calls")
+        job.fused_save = True
+        two = job.move_figures(sprof)
+        one = job.move_figures(hprof, fused_device_tier=True)
         hbm = dict(ms_per_step=hdt / args.hbm_steps * 1e3, tokens_per_s=job.tot_q / (hdt / args.hbm_steps),
-                   context_tokens_per_s=job.tot_k / (hdt / args.hbm_steps), attn=job.attn_figures(h_att), kv_move=job.move_figures(hprof),
+                   context_tokens_per_s=job.tot_k / (hdt / args.hbm_steps), attn=job.attn_figures(h_att), kv_move=one,
+                   append_save=dict(one_call_in_step_us=one["append"]["avg_launch_us"],
+                                    two_calls_in_step_us=(two["append"]["avg_launch_us"] or 0) + (two["pack"]["avg_launch_us"] or 0),
+                                    ms_per_step_two_calls=sdt * 1e3,
+                                    note="the new turn appended and saved by one kernel that reads it once (N in, 2N out), "
+                                         "against the append kernel plus the pack kernel (2N in, 2N out)"),
                    note="same entry points; the load kernel reads the tier in place from device memory, no host link in the step")
     iso = job.isolated(ctx, dev_k if want_hbm else src_k, dev_v if want_hbm else src_v, stream)
     log("[bench] isolated: " + ", ".join(f"{k} {v['avg_launch_us']:.1f} us" for k, v in iso.items()))

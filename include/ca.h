@@ -101,6 +101,12 @@ typedef struct {
                              /* scratch copy first.  0: decide per batch (three or more 256-row  */
                              /* tiles per (conversation, kv head) on average); 1: never;         */
                              /* 2: always (256-row tiles are then used whatever the batch)       */
+    int32_t attn_schedule;   /* 0: the LDS-direct kernel, all wavefronts of a workgroup in lock step.      */
+                             /* 1: when the keys are rotated once per layer (attn_prerotate), head_dim is  */
+                             /* 128 and the tiles have 256 rows, the values are transposed into a scratch  */
+                             /* copy in the same pass and a kernel runs that pipelines, inside every       */
+                             /* wavefront, the matrix instructions of one key tile with the softmax of the */
+                             /* previous one (any window; measured as fast as 0, plus the longer pre-pass)  */
     int32_t require_load;    /* 1: attention on a layer with kept history that was not loaded */
                              /* under the current plan fails with CA_ERR_NOT_READY            */
     int32_t device;          /* HIP device ordinal                                            */
@@ -238,6 +244,18 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
                            const int32_t *tok_end, const void *k_pool, const void *v_pool,
                            void *const *dst_k, void *const *dst_v, const int64_t *dst_tok_offset,
                            void *after_stream);
+
+/* ca_kv_append_layer and ca_kv_save_layer (default range and offset: the new tokens go behind the
+ * saved history of every conversation) in one call that reads new_k / new_v once: what is saved IS
+ * what is appended, keys without positional encoding (Sections 3.2.2, 3.4), so the pool is not read
+ * back.  Device destinations (and pinned ones under save_mode 2): one kernel on `stream` stores every
+ * vector twice, to its page and to its row of the tier.  Pinned destinations otherwise: the append
+ * kernel runs on `stream` and the copy-out follows on the internal save stream straight from new_k /
+ * new_v (no pack kernel, no staging slot); new_k / new_v must then stay unchanged until ca_sync or
+ * ca_join.  Same arguments, checks and statuses as the two calls it replaces.                      */
+ca_status ca_kv_append_save_layer(ca_ctx *ctx, int32_t layer, const void *new_k, const void *new_v,
+                                  void *k_pool, void *v_pool, void *const *dst_k, void *const *dst_v,
+                                  void *stream);
 
 /* Blocks the host until the internal streams are idle. */
 ca_status ca_sync(ca_ctx *ctx);

@@ -23,7 +23,7 @@ STATUS = {0: "CA_OK", 1: "CA_ERR_INVALID_ARG", 2: "CA_ERR_OUT_OF_RANGE", 3: "CA_
 SYMBOLS = ["ca_config_default", "ca_config_validate", "ca_batch_validate", "ca_create", "ca_destroy",
            "ca_last_error", "ca_status_string", "ca_truncate_plan", "ca_truncate_plan_sinks", "ca_rope_rebase", "ca_rebase_read",
            "ca_kv_load_layer", "ca_kv_append_layer", "ca_cached_prefill_attn", "ca_cached_prefill_attn_static",
-           "ca_kv_save_layer",
+           "ca_kv_save_layer", "ca_kv_append_save_layer",
            "ca_sync", "ca_join", "ca_profile_enable", "ca_profile_read"]
 
 
@@ -41,7 +41,7 @@ class _CConfig(C.Structure):
                 ("max_seqs", C.c_int32), ("max_batch_kv_tokens", C.c_int64),
                 ("max_batch_q_tokens", C.c_int64), ("load_mode", C.c_int32), ("save_mode", C.c_int32),
                 ("attn_variant", C.c_int32), ("attn_tile_rows", C.c_int32), ("attn_split", C.c_int32),
-                ("attn_prerotate", C.c_int32), ("require_load", C.c_int32),
+                ("attn_prerotate", C.c_int32), ("attn_schedule", C.c_int32), ("require_load", C.c_int32),
                 ("device", C.c_int32)]
 
 
@@ -100,6 +100,8 @@ def load_library():
     # the three optional per-conversation arrays go in as plain addresses (cheaper to marshal per call)
     lib.ca_kv_save_layer.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.POINTER(vp), C.POINTER(vp), vp, vp]
     lib.ca_kv_save_layer.restype = C.c_int
+    lib.ca_kv_append_save_layer.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.ca_kv_append_save_layer.restype = C.c_int
     lib.ca_sync.argtypes = [vp]
     lib.ca_sync.restype = C.c_int
     lib.ca_join.argtypes = [vp, vp]
@@ -132,6 +134,7 @@ class Config:
     attn_tile_rows: int = 0
     attn_split: int = 0
     attn_prerotate: int = 0
+    attn_schedule: int = 0
     require_load: int = 1
     device: int = 0
 
@@ -335,6 +338,13 @@ class Context:
         tb, te, off = opt(tok_begin, np.int32), opt(tok_end, np.int32), opt(dst_tok_offset, np.int64)
         self._check(self._lib.ca_kv_save_layer(self._h, int(layer), tb, te, _ptr(k_pool), _ptr(v_pool), ak, av,
                                                off, _stream(after_stream)))
+
+    def kv_append_save_layer(self, layer: int, new_k, new_v, k_pool, v_pool, dst_k, dst_v, stream=None):
+        ak, av = self._ptr_array(dst_k), self._ptr_array(dst_v)
+        if self.n_seqs and (len(ak) != self.n_seqs or len(av) != self.n_seqs):
+            raise ValueError("dst_k/dst_v need one pointer per conversation of the current plan")
+        self._check(self._lib.ca_kv_append_save_layer(self._h, int(layer), _ptr(new_k), _ptr(new_v), _ptr(k_pool),
+                                                      _ptr(v_pool), ak, av, _stream(stream)))
 
     def sync(self):
         self._check(self._lib.ca_sync(self._h))

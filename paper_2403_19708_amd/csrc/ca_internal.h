@@ -24,6 +24,14 @@ struct MoveArgs {
     int32_t seq[kMaxSeqsPerLaunch];  // row of the block table
 };
 
+// Second contiguous destination of a launch that writes what it reads twice (the new turn's K/V go into the pool AND
+// to the tier in one pass): token (contig_tok0 + i) of the source also lands at token (dst2_tok0 + i) of dst2.
+struct MoveArgs2 {
+    uint8_t *dst2_k[kMaxSeqsPerLaunch];
+    uint8_t *dst2_v[kMaxSeqsPerLaunch];
+    int64_t dst2_tok0[kMaxSeqsPerLaunch];
+};
+
 constexpr int kMoveUnroll = 2;   // 16-byte loads in flight per lane of the move kernel (one pass = kMoveUnroll*256 vectors)
 
 struct MoveShape {
@@ -39,6 +47,9 @@ struct MoveShape {
 // to_pool = true: contiguous -> pages (unpack / append); false: pages -> contiguous (pack).
 hipError_t launch_move(bool to_pool, const MoveArgs &args, const MoveShape &shape, uint8_t *k_pool,
                        uint8_t *v_pool, hipStream_t stream);
+// contiguous -> pages as launch_move(true, ...), and every vector is also stored to the second destination
+hipError_t launch_move_dual(const MoveArgs &args, const MoveArgs2 &second, const MoveShape &shape, uint8_t *k_pool,
+                            uint8_t *v_pool, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
 // Section 3.4: per-token metadata of the rebased plan
@@ -94,6 +105,9 @@ struct AttnArgs {
     const float2 *rope;      // [max_positions][head_dim/2] (cos, sin)
     // keys rotated once per batch and layer instead of in every row tile (prerotate != 0):
     uint16_t *k_rot;             // scratch copy of the keys, dense pages [n_dense_pages][n_kv_heads][16][head_dim]
+    uint16_t *v_t;               // scratch copy of the values, same pages, each block transposed (pipelined != 0 only)
+    const int32_t *rot_nvalid;   // [n_dense_pages] context tokens in the page (16 except a conversation's last page)
+    int32_t pipelined;            // the scratch copies have the layouts of ca_attn_pp.hip and its kernel runs
     const int32_t *dense_page0;  // [n_seqs] first dense page of a conversation
     const int32_t *rot_src_page; // [n_dense_pages] pool page a dense page is rotated from
     const int32_t *rot_pos0;     // [n_dense_pages] position of its first token
@@ -116,6 +130,9 @@ constexpr int kRopeMinRows = 256;       // the kernels read table rows below thi
 hipError_t launch_attn_mfma(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_ref(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_dma(const AttnArgs &args, hipStream_t stream);
+// head_dim 128, 256-row tiles, keys rotated and values transposed once per layer into scratch copies; inside every
+// wavefront the matrix instructions of one key tile are pipelined with the softmax of the previous one
+hipError_t launch_attn_pp(const AttnArgs &args, hipStream_t stream);
 // merges the shares of split row tiles (args.combine) into args.out; used by every kernel that writes shares
 hipError_t launch_attn_combine(const AttnArgs &args, hipStream_t stream);
 // decode steps: every item has at most kAttnDecodeMaxRows stacked rows starting at row 0; streams K/V through

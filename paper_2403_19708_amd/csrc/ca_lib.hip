@@ -49,6 +49,9 @@ struct ca_ctx {
     size_t items_capacity = 0;         // work items the image has room for
     float *partial = nullptr;          // shares of row tiles whose keys were split over workgroups
     uint16_t *k_rot = nullptr;         // keys of the batch context rotated once per layer (dense pages)
+    uint16_t *v_t = nullptr;           // values of the batch context transposed once per layer (same pages)
+    bool pipelined = false;             // the plan runs the software-pipelined kernel on the two scratch copies
+    size_t off_rot_nvalid = 0;
     size_t k_rot_pages = 0;
     size_t off_dense0 = 0, off_rot_src = 0, off_rot_pos = 0;
     int32_t n_dense_pages = 0;
@@ -209,6 +212,7 @@ void ca_config_default(ca_config *c) {
     c->attn_tile_rows = 0;
     c->attn_split = 0;
     c->attn_prerotate = 0;
+    c->attn_schedule = 0;
     c->require_load = 1;
     c->device = 0;
 }
@@ -273,6 +277,7 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
         return CA_ERR_UNSUPPORTED;
     }
     if (c->attn_prerotate < 0 || c->attn_prerotate > 2) { set_err(err, err_len, "attn_prerotate must be 0, 1 or 2"); return CA_ERR_INVALID_ARG; }
+    if (c->attn_schedule < 0 || c->attn_schedule > 1) { set_err(err, err_len, "attn_schedule must be 0 or 1"); return CA_ERR_INVALID_ARG; }
     if (c->attn_split < 0 || c->attn_split > 1) { set_err(err, err_len, "attn_split must be 0 or 1"); return CA_ERR_INVALID_ARG; }
     if (c->device < 0) { set_err(err, err_len, "device < 0"); return CA_ERR_INVALID_ARG; }
     return CA_OK;
@@ -458,6 +463,7 @@ void ca_destroy(ca_ctx *ctx) {
     if (ctx->rope) (void)hipFree(ctx->rope);
     if (ctx->partial) (void)hipFree(ctx->partial);
     if (ctx->k_rot) (void)hipFree(ctx->k_rot);
+    if (ctx->v_t) (void)hipFree(ctx->v_t);
     if (ctx->d_meta) (void)hipFree(ctx->d_meta);
     if (ctx->h_meta) (void)hipHostFree(ctx->h_meta);
     if (ctx->s_copy) (void)hipStreamDestroy(ctx->s_copy);
@@ -538,6 +544,7 @@ static ca_status create_impl(ca_ctx *ctx) {
         ctx->off_dense0 = off;  off = align_up(off + (size_t)c.max_seqs * 4, 256);
         ctx->off_rot_src = off; off = align_up(off + ctx->k_rot_pages * 4, 256);
         ctx->off_rot_pos = off; off = align_up(off + ctx->k_rot_pages * 4, 256);
+        ctx->off_rot_nvalid = off; off = align_up(off + ctx->k_rot_pages * 4, 256);
         ctx->off_combine = off; off = align_up(off + (size_t)kAttnMaxParts * sizeof(CombineItem), 256);
         ctx->off_items = off;   off = align_up(off + max_items_padded * sizeof(WorkItem), 256);
         ctx->upload_bytes = off;
@@ -555,8 +562,11 @@ static ca_status create_impl(ca_ctx *ctx) {
         CA_HIP(ctx, hipMalloc((void **)&ctx->partial, bytes));
     }
     const bool may_direct = direct_variant(c);
-    if (may_direct && c.attn_prerotate != 1)
+    if (may_direct && c.attn_prerotate != 1) {
         CA_HIP(ctx, hipMalloc((void **)&ctx->k_rot, ctx->k_rot_pages * (size_t)c.page_size * (size_t)row_bytes(c)));
+        if (c.head_dim == 128 && c.attn_schedule == 1)
+            CA_HIP(ctx, hipMalloc((void **)&ctx->v_t, ctx->k_rot_pages * (size_t)c.page_size * (size_t)row_bytes(c)));
+    }
     {
         hipDeviceProp_t prop;
         CA_HIP(ctx, hipGetDeviceProperties(&prop, c.device));
@@ -702,8 +712,10 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
             ctx->prerotate = ctx->k_rot && direct_for_rot &&
                              (c.attn_prerotate == 2 || (c.attn_prerotate == 0 && tiles256 >= (int64_t)3 * B));
             if (ctx->prerotate && c.attn_tile_rows == 0) tile = 256;
+            ctx->pipelined = ctx->prerotate && ctx->v_t && tile == 256 && c.attn_variant != 3 && c.attn_variant != 1;
             int32_t *dense0 = (int32_t *)(ctx->h_meta + ctx->off_dense0);
             int32_t *rot_src = (int32_t *)(ctx->h_meta + ctx->off_rot_src), *rot_pos = (int32_t *)(ctx->h_meta + ctx->off_rot_pos);
+            int32_t *rot_nvalid = (int32_t *)(ctx->h_meta + ctx->off_rot_nvalid);
             int32_t at = 0;
             for (int i = 0; i < B; ++i) {
                 dense0[i] = at;
@@ -712,6 +724,7 @@ ca_status ca_rope_rebase(ca_ctx *ctx, const ca_batch *b, void *stream_) {
                 for (int p = 0; p < pages; ++p, ++at) {
                     rot_src[at] = b->block_table[(int64_t)i * b->max_pages + p];
                     rot_pos[at] = p * c.page_size;
+                    rot_nvalid[at] = std::min(c.page_size, ctx->n_keep[i] + b->new_len[i] - p * c.page_size);
                 }
             }
             if ((size_t)at > ctx->k_rot_pages) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_rope_rebase: internal: %d dense pages exceed %zu", at, ctx->k_rot_pages);
@@ -1176,6 +1189,97 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
     return CA_OK;
 }
 
+// Appending and saving the new turn in one call: the saved bytes ARE the appended bytes (keys without positions,
+// Section 3.4), so the pool need not be read back.  Device-accessible destinations: one kernel reads new_k/new_v once
+// and stores every vector twice (pool and tier).  Pinned destinations with staged saving: the copy-out on the save
+// stream reads new_k/new_v directly; no pack kernel, no staging slot.
+ca_status ca_kv_append_save_layer(ca_ctx *ctx, int32_t layer, const void *new_k, const void *new_v, void *k_pool,
+                                  void *v_pool, void *const *dst_k, void *const *dst_v, void *stream_) {
+    if (!ctx) return CA_ERR_INVALID_ARG;
+    ca_status st = check_layer_plan(ctx, "ca_kv_append_save_layer", layer);
+    if (st != CA_OK) return st;
+    if (!dst_k || !dst_v) return fail(ctx, CA_ERR_INVALID_ARG, "ca_kv_append_save_layer: destination pointer array is NULL");
+    const ca_config &c = ctx->cfg;
+    CA_HIP(ctx, hipSetDevice(c.device));
+    st = check_pools(ctx, "ca_kv_append_save_layer", k_pool, v_pool);
+    if (st != CA_OK) return st;
+    const int64_t rb = row_bytes(c);
+    const size_t bytes = (size_t)ctx->total_q * (size_t)rb;
+    if (!device_range_ok(new_k, bytes) || !device_range_ok(new_v, bytes))
+        return fail(ctx, CA_ERR_INVALID_ARG, "ca_kv_append_save_layer: new_k/new_v must be device memory of %zu bytes", bytes);
+    const int B = ctx->n_seqs;
+    bool any_host = false;
+    for (int i = 0; i < B; ++i) {
+        if (!dst_k[i] || !dst_v[i]) return fail(ctx, CA_ERR_INVALID_ARG, "ca_kv_append_save_layer: destination of conversation %d is NULL", i);
+        const MemKind kk = mem_kind(dst_k[i]), kv = mem_kind(dst_v[i]);
+        if (kk == MemKind::kUnknown || kv == MemKind::kUnknown)
+            return fail(ctx, CA_ERR_INVALID_ARG, "ca_kv_append_save_layer: destination of conversation %d is neither pinned host nor device memory", i);
+        if (kk == MemKind::kPinnedHost || kv == MemKind::kPinnedHost) any_host = true;
+        const size_t need = (size_t)(ctx->hist_len[i] + ctx->new_len[i]) * rb;
+        if ((kk == MemKind::kDevice && !device_range_ok(dst_k[i], need)) || (kv == MemKind::kDevice && !device_range_ok(dst_v[i], need)))
+            return fail(ctx, CA_ERR_INVALID_ARG, "ca_kv_append_save_layer: destination of conversation %d is smaller than hist_len + new_len tokens", i);
+    }
+    const bool staged = c.save_mode == 1 || (c.save_mode == 0 && any_host);
+    hipStream_t stream = (hipStream_t)stream_;
+    if (staged) {
+        // append on the caller's stream; the copy-out follows it on the save stream, straight from new_k / new_v
+        std::vector<Segment> segs;
+        for (int i = 0; i < B; ++i)
+            segs.push_back({(uint8_t *)new_k, (uint8_t *)new_v, ctx->cu_q[i], ctx->n_keep[i], ctx->new_len[i], i});
+        int iv;
+        CA_HIP(ctx, prof_begin(ctx, kProfAppend, stream, &iv));
+        st = run_move(ctx, true, segs, k_pool, v_pool, stream);
+        if (st != CA_OK) return st;
+        CA_HIP(ctx, prof_end(ctx, iv, stream));
+        CA_HIP(ctx, hipEventRecord(ctx->ev_after, stream));
+        CA_HIP(ctx, hipStreamWaitEvent(ctx->s_save, ctx->ev_after, 0));
+        int iv_out;
+        CA_HIP(ctx, prof_begin(ctx, kProfCopyOut, ctx->s_save, &iv_out));
+        for (int i = 0; i < B; ++i) {
+            const size_t n = (size_t)ctx->new_len[i] * rb, src_off = (size_t)ctx->cu_q[i] * rb, dst_off = (size_t)ctx->hist_len[i] * rb;
+            CA_HIP(ctx, hipMemcpyAsync((uint8_t *)dst_k[i] + dst_off, (const uint8_t *)new_k + src_off, n, hipMemcpyDefault, ctx->s_save));
+            CA_HIP(ctx, hipMemcpyAsync((uint8_t *)dst_v[i] + dst_off, (const uint8_t *)new_v + src_off, n, hipMemcpyDefault, ctx->s_save));
+        }
+        CA_HIP(ctx, prof_end(ctx, iv_out, ctx->s_save));
+        return CA_OK;
+    }
+    // one pass: every vector of the new turn goes to its page and to its row of the tier
+    MoveShape shape{};
+    shape.block_table = (const int32_t *)(ctx->d_meta + ctx->off_table);
+    shape.max_pages = ctx->max_pages;
+    shape.n_kv_heads = c.n_kv_heads;
+    shape.vecs_per_row = c.head_dim * 2 / 16;
+    shape.heads_per_wg = std::max(1, std::min(c.n_kv_heads, kMoveUnroll * 256 / (16 * shape.vecs_per_row)));
+    int iv;
+    CA_HIP(ctx, prof_begin(ctx, kProfAppend, stream, &iv));
+    for (int at = 0; at < B; at += kMaxSeqsPerLaunch) {
+        MoveArgs args;
+        MoveArgs2 second;
+        std::memset(&args, 0, sizeof args);
+        std::memset(&second, 0, sizeof second);
+        const int n = std::min(kMaxSeqsPerLaunch, B - at);
+        int max_touched = 0;
+        for (int i = 0; i < n; ++i) {
+            const int q = at + i;
+            args.contig_k[i] = (uint8_t *)new_k;
+            args.contig_v[i] = (uint8_t *)new_v;
+            args.contig_tok0[i] = ctx->cu_q[q];
+            args.ctx_tok0[i] = ctx->n_keep[q];
+            args.count[i] = ctx->new_len[q];
+            args.seq[i] = q;
+            second.dst2_k[i] = (uint8_t *)dst_k[q];
+            second.dst2_v[i] = (uint8_t *)dst_v[q];
+            second.dst2_tok0[i] = ctx->hist_len[q];       // new token j is saved behind the history, at token hist_len + j
+            max_touched = std::max(max_touched, (ctx->n_keep[q] + ctx->new_len[q] - 1) / kPageSize - ctx->n_keep[q] / kPageSize + 1);
+        }
+        shape.n_in_launch = n;
+        shape.max_pages_touched = max_touched;
+        CA_HIP(ctx, launch_move_dual(args, second, shape, (uint8_t *)k_pool, (uint8_t *)v_pool, stream));
+    }
+    CA_HIP(ctx, prof_end(ctx, iv, stream));
+    return CA_OK;
+}
+
 // ----------------------------------------------------------------------------------------------
 // Sections 2.1 / 3.1 / 3.4: attention of the new tokens
 // ----------------------------------------------------------------------------------------------
@@ -1217,6 +1321,9 @@ static ca_status attn_impl(ca_ctx *ctx, int32_t layer, const void *q, const void
     a.dense_page0 = (const int32_t *)(ctx->d_meta + ctx->off_dense0);
     a.rot_src_page = (const int32_t *)(ctx->d_meta + ctx->off_rot_src);
     a.rot_pos0 = (const int32_t *)(ctx->d_meta + ctx->off_rot_pos);
+    a.v_t = ctx->v_t;
+    a.rot_nvalid = (const int32_t *)(ctx->d_meta + ctx->off_rot_nvalid);
+    a.pipelined = ctx->pipelined ? 1 : 0;
     a.n_dense_pages = ctx->n_dense_pages;
     a.prerotate = ctx->prerotate ? 1 : 0;
     a.max_positions = c.max_positions;
@@ -1247,6 +1354,8 @@ static ca_status attn_impl(ca_ctx *ctx, int32_t layer, const void *q, const void
         CA_HIP(ctx, launch_attn_ref(a, stream));
     } else if (decode) {
         CA_HIP(ctx, launch_attn_decode(a, ctx->max_unit_rows, stream));
+    } else if (direct && ctx->pipelined) {
+        CA_HIP(ctx, launch_attn_pp(a, stream));
     } else if (direct) {
         CA_HIP(ctx, launch_attn_dma(a, stream));
     } else {

@@ -28,10 +28,12 @@ constexpr int kMoveMaxGridY = 32768;
 // page run next to each other and both sides of the copy see long sequential runs; with few loads
 // in flight per lane and keys and values in separate workgroups the kernel reaches 5.7 TB/s on a
 // 337 MB load where the opposite choices (pages fastest, 4 + 4 loads per lane) gave 5.0.
-template <bool kToPool, bool kNT>
-__global__ __launch_bounds__(kMoveThreads) void move_kernel(MoveArgs a, MoveShape s,
-                                                            uint8_t *__restrict__ k_pool,
-                                                            uint8_t *__restrict__ v_pool) {
+// kDual (with kToPool): every vector read from the contiguous side is stored twice, into the pool and into a second
+// contiguous destination (the tier): the new turn's K/V are appended and saved in one pass over them.
+template <bool kToPool, bool kNT, bool kDual>
+__device__ inline void move_body(const MoveArgs &a, const MoveShape &s, uint8_t *__restrict__ k_pool,
+                                 uint8_t *__restrict__ v_pool, const MoveArgs2 &b) {
+    static_assert(!kDual || kToPool, "the second destination goes with contiguous -> pages");
     const int e = blockIdx.z;  // entry of this launch
     const bool values = blockIdx.x & 1;
     const int ctx_begin = a.ctx_tok0[e];
@@ -53,6 +55,8 @@ __global__ __launch_bounds__(kMoveThreads) void move_kernel(MoveArgs a, MoveShap
         const int64_t contig_first = a.contig_tok0[e] + (t_first - ctx_begin);
         vec16 *contig = reinterpret_cast<vec16 *>(values ? a.contig_v[e] : a.contig_k[e]) + contig_first * row_vecs + (int64_t)h_first * vpr;
         vec16 *pool = reinterpret_cast<vec16 *>(values ? v_pool : k_pool) + (((int64_t)page * H + h_first) * kPageSize + slot0) * vpr;
+        vec16 *second = nullptr;
+        if (kDual) second = reinterpret_cast<vec16 *>(values ? b.dst2_v[e] : b.dst2_k[e]) + (b.dst2_tok0[e] + (t_first - ctx_begin)) * row_vecs + (int64_t)h_first * vpr;
 
         // vector id v -> (head, token, 16-byte piece), piece fastest
         const int per_head = n_tok * vpr;
@@ -83,10 +87,22 @@ __global__ __launch_bounds__(kMoveThreads) void move_kernel(MoveArgs a, MoveShap
                 if (live[u]) {
                     vec16 *dst = kToPool ? pool + pool_idx[u] : contig + contig_idx[u];
                     if (kNT) __builtin_nontemporal_store(r[u], dst); else *dst = r[u];
+                    if (kDual) __builtin_nontemporal_store(r[u], second + contig_idx[u]);
                 }
             }
         }
     }
+}
+
+template <bool kToPool, bool kNT>
+__global__ __launch_bounds__(kMoveThreads) void move_kernel(MoveArgs a, MoveShape s, uint8_t *__restrict__ k_pool,
+                                                            uint8_t *__restrict__ v_pool) {
+    move_body<kToPool, kNT, false>(a, s, k_pool, v_pool, MoveArgs2{});
+}
+
+__global__ __launch_bounds__(kMoveThreads) void move_dual_kernel(MoveArgs a, MoveArgs2 b, MoveShape s, uint8_t *__restrict__ k_pool,
+                                                                 uint8_t *__restrict__ v_pool) {
+    move_body<true, true, true>(a, s, k_pool, v_pool, b);
 }
 
 // One thread per context token: which conversation it belongs to (binary search in the prefix
@@ -123,6 +139,15 @@ hipError_t launch_move(bool to_pool, const MoveArgs &args, const MoveShape &shap
         hipLaunchKernelGGL((move_kernel<true, true>), grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);
     else
         hipLaunchKernelGGL((move_kernel<false, true>), grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);
+    return hipGetLastError();
+}
+
+hipError_t launch_move_dual(const MoveArgs &args, const MoveArgs2 &second, const MoveShape &shape, uint8_t *k_pool,
+                            uint8_t *v_pool, hipStream_t stream) {
+    if (shape.n_in_launch <= 0 || shape.max_pages_touched <= 0) return hipSuccess;
+    const int slices = (shape.n_kv_heads + shape.heads_per_wg - 1) / shape.heads_per_wg;
+    dim3 grid(2 * slices, std::min(shape.max_pages_touched, kMoveMaxGridY), shape.n_in_launch);
+    hipLaunchKernelGGL(move_dual_kernel, grid, dim3(kMoveThreads), 0, stream, args, second, shape, k_pool, v_pool);
     return hipGetLastError();
 }
 

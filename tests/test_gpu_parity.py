@@ -151,11 +151,17 @@ def test_save_arbitrary_ranges_bit_exact(case):
 
 
 def variant_config(variant):
-    """12 stands for the LDS-direct kernel (2) reading keys that were rotated once into a scratch copy"""
-    return dict(attn_variant=2, attn_prerotate=2) if variant == 12 else dict(attn_variant=variant)
+    """12: keys rotated (and, for head_dim 128, values transposed) once per layer into scratch copies, read by the
+    kernel that pipelines matrix instructions and softmax inside each wavefront; 13: the rotated keys read by the
+    LDS-direct kernel (2) with all wavefronts in lock step"""
+    if variant == 12:
+        return dict(attn_variant=2, attn_prerotate=2, attn_schedule=1)
+    if variant == 13:
+        return dict(attn_variant=2, attn_prerotate=2)
+    return dict(attn_variant=variant)
 
 
-@pytest.mark.parametrize("variant", [1, 3, 2, 12], ids=["scalar", "staged", "direct", "direct-prerotated"])
+@pytest.mark.parametrize("variant", [1, 3, 2, 12, 13], ids=["scalar", "staged", "direct", "pipelined", "direct-prerotated"])
 def test_attention_matches_oracle(case, variant):
     run = GpuRun(case, tier="device", **variant_config(variant))
     try:
@@ -201,7 +207,7 @@ def test_small_batch_splits_keys_over_workgroups(shape, split):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [2, 3, 12], ids=["direct", "staged", "direct-prerotated"])
+@pytest.mark.parametrize("variant", [2, 3, 12, 13], ids=["direct", "staged", "pipelined", "direct-prerotated"])
 def test_context_fills_the_largest_window_of_the_direct_kernel(variant):
     """One conversation whose context is exactly 32768 tokens: every entry of the LDS-direct kernel's page
     table is in use, the last tile ends on the window, positions reach 32767 (and the few row tiles of a
@@ -257,7 +263,7 @@ def test_default_variant_follows_the_window(window):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [1, 3, 2, 12], ids=["scalar", "staged", "direct", "direct-prerotated"])
+@pytest.mark.parametrize("variant", [1, 3, 2, 12, 13], ids=["scalar", "staged", "direct", "pipelined", "direct-prerotated"])
 def test_attention_peaky_softmax(variant):
     """Queries scaled x6: a handful of keys dominate each row and outputs are O(1), so a wrong key,
     a wrong mask edge or a wrong position cannot hide under the tolerance.  Scores grow with the
@@ -282,13 +288,38 @@ def test_attention_peaky_softmax(variant):
                 Kr = np.array([[oracle.rope(K[t, g], t) for g in range(K.shape[1])] for t in range(K.shape[0])])
                 Qr = np.array([[oracle.rope(Q[j, h], n + j) for h in range(Q.shape[1])] for j in range(ln)])
                 Kr = w(f32_to_bf16_bits(Kr.astype(np.float32)))
-                Qr = w(f32_to_bf16_bits(Qr.astype(np.float32)))
+                if variant == 12:
+                    # this kernel folds softmax scale * log2(e) into the rotated query before rounding it; dividing
+                    # the rounded value by the same factor gives the oracle exactly the scores the kernel forms
+                    fold = np.float32(1.0 / np.sqrt(case.head_dim)) * np.float32(1.4426950408889634)
+                    Qr = w(f32_to_bf16_bits(Qr.astype(np.float32) * fold)) / np.float64(fold)
+                else:
+                    Qr = w(f32_to_bf16_bits(Qr.astype(np.float32)))
                 want = oracle.attention_positions(Kr, V, Qr, np.zeros(K.shape[0]), np.zeros(ln), n)
             else:   # the scalar kernel keeps the rotated values in fp32
                 want = case.oracle_out(0, c)
             got = run.out_f64(0, c)
             assert np.sqrt(np.mean(want ** 2)) > 0.5
             check_contract(got, want, c)
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("variant", [3, 2, 12, 13], ids=["staged", "direct", "pipelined", "direct-prerotated"])
+def test_attention_peaky_softmax_against_the_plain_oracle(variant):
+    """Queries scaled x2: rows rest on a few keys and outputs are O(1), and at this scale the bf16 rounding of the
+    rotated Q/K still leaves the kernels inside the contract against the oracle as it stands (no rounding point
+    applied to the reference)."""
+    case = Case([210, 64], [75, 130], [31, 0], 4, 2, 128, seed=11, q_scale=2.0)
+    run = GpuRun(case, tier="device", **variant_config(variant))
+    try:
+        run.rebase()
+        run.run_layer(0)
+        run.finish()
+        for c in range(case.B):
+            want = case.oracle_out(0, c)
+            assert np.sqrt(np.mean(want ** 2)) > 0.25
+            check_contract(run.out_f64(0, c), want, c)
     finally:
         run.close()
 

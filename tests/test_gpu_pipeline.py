@@ -100,10 +100,10 @@ def test_next_job_preloads_while_the_current_job_computes():
         a.close(); b.close()
 
 
-@pytest.mark.parametrize("variant", [3, 2, 12], ids=["staged", "direct", "direct-prerotated"])
+@pytest.mark.parametrize("variant", [3, 2, 12, 13], ids=["staged", "direct", "pipelined", "direct-prerotated"])
 def test_both_tile_sizes_agree_with_oracle(variant):
     case = Case([500, 90], [200, 31], [37, 0], 8, 2, 128, seed=52)
-    more = dict(variant=2, attn_prerotate=2) if variant == 12 else dict(variant=variant)
+    more = dict(variant=2, attn_prerotate=2, attn_schedule=int(variant == 12)) if variant in (12, 13) else dict(variant=variant)
     for tile in (128, 256):
         out, _ = run_stack(case, "device", 2, 0, tile=tile, **more)
         at = 0
