@@ -690,7 +690,7 @@ def main():
     kv_move = job.move_figures(prof_i)
 
     # the dominant kernel of the step by GPU time: the attention call
-    attn_kernel = "attn_dma_kernel" if job.W <= 32768 else "attn_mfma_kernel"
+    attn_kernel = "attn_dma_kernel"
     G = job.Hq // job.Hkv
     # the library rotates the keys once per layer when on average three or more 256-row tiles share them
     prerot = job.W <= 32768 and int(np.sum((job.new.astype(np.int64) * G + 255) // 256)) >= 3 * job.B

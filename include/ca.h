@@ -81,14 +81,13 @@ typedef struct {
     int32_t save_mode;       /* like load_mode, for ca_kv_save_layer: 0 choose per destination  */
                              /* (pinned host: staging slot + copy-out), 1 always stage, 2 the   */
                              /* pack kernel writes the destination in place                     */
-    int32_t attn_variant;    /* 0: choose (4 for a batch it fits, else 2, when max_positions    */
-                             /* <= 32768; else 3); 1: scalar fp32 kernel (slow, for checking);  */
-                             /* 2: MFMA kernel, K/V loaded straight into LDS (needs             */
-                             /* max_positions <= 32768); 3: MFMA kernel, K/V staged through     */
-                             /* registers (any window); 4: as 2, but a batch in which every     */
-                             /* (conversation, kv head) has at most 2 stacked query rows (a     */
-                             /* decode step) takes the streaming kernel, and any other batch is */
-                             /* refused by ca_cached_prefill_attn with CA_ERR_UNSUPPORTED       */
+    int32_t attn_variant;    /* 0: choose (the streaming kernel for a batch of decode steps, else the    */
+                             /* matrix-core kernel); 1: scalar fp32 kernel (slow, for checking); 2: the  */
+                             /* matrix-core kernel, K/V loaded straight into LDS, whatever the batch;    */
+                             /* 4: as 0, but a batch in which some (conversation, kv head) has more than */
+                             /* 2 stacked query rows (not a decode step) is refused by                   */
+                             /* ca_cached_prefill_attn with CA_ERR_UNSUPPORTED.  (3 named a second       */
+                             /* matrix-core kernel that was removed; it is refused.)                     */
     int32_t attn_tile_rows;  /* stacked query rows per workgroup of the MFMA kernel: 128, 256,  */
                              /* or 0 = choose per batch                                        */
     int32_t attn_split;      /* 0: when a batch has too few row tiles to keep all compute units */

@@ -14,7 +14,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["ca_lib.hip", "ca_move.hip", "ca_attn_ref.hip", "ca_attn_mfma.hip", "ca_attn_dma.hip", "ca_attn_pp.hip", "ca_attn_decode.hip",
+SOURCES = ["ca_lib.hip", "ca_move.hip", "ca_attn_ref.hip", "ca_attn_dma.hip", "ca_attn_pp.hip", "ca_attn_decode.hip",
            "ca_store.cpp"]   # the last one is host code only (placement manager)
 LIB = os.path.join(HERE, "libca_hip.so")
 

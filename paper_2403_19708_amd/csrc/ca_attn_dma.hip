@@ -1,16 +1,20 @@
-// Fused rotary-on-load + causal varlen prefill attention (Sections 2.1, 3.1, 3.4), variant whose
-// K/V tiles travel HBM -> LDS without passing through registers.
+// Fused rotary-on-load + causal varlen prefill attention (Sections 2.1, 3.1, 3.4) on the matrix cores.
 //
-// Same mathematics, work decomposition (8 wavefronts x 32 stacked query rows, key tiles of 64) and
-// matrix-core formulation (S^T = K Q^T, O^T += V^T P^T with v_mfma_f32_32x32x16_bf16) as
-// ca_attn_mfma.hip.  What differs is the memory pipeline:
+// out[j, h, :] = sum_t softmax_t(RoPE(q[j,h], n+j) . RoPE(k[t], t) * scale) v[t] over the context tokens t <= n + j of
+// the conversation, bf16 in, fp32 accumulate, bf16 out.  One workgroup = NW wavefronts x 32 stacked query rows (row r
+// of a (conversation, kv head) <-> new token r / G, query head kv*G + r % G, so the G heads of a group share every
+// staged K/V tile), walking key tiles of BN with an online softmax.  v_mfma_f32_32x32x16_bf16 in the transposed
+// formulation S^T = K Q^T, O^T += V^T P^T: in the C layout a lane owns one query column, so row maxima and sums are
+// in-lane plus one exchange with lane ^ 32, and the C registers of S^T, converted to bf16, ARE the B operand of the
+// second product.  The reference maximum is raised lazily (a wave-uniform branch, rare after the first tile).
+// K/V tiles travel HBM -> LDS without passing through registers:
 //
 //   * global_load_lds (16 bytes per lane, written to LDS at base + lane*16) fills a ring of 4 tile
 //     stages in LDS; the loads of tile T+3 are issued when tile T starts, so two to three tiles
 //     (64-96 KiB per compute unit) are in flight while one is multiplied, and no vector register
 //     is spent on staging.  The only vector-memory instructions inside the walk are these loads,
 //     so s_waitcnt vmcnt(N) with a constant N releases exactly the tile that is needed next.
-//   * The page ids of the conversation are copied into LDS once; the dependent chain
+//   * The page ids of the conversation are kept in LDS (a window of 2048 pages that follows the walk); the dependent chain
 //     block table -> page -> row costs an LDS read.  On interior tiles a load's page and base address
 //     are wave-uniform: all page ids of an iteration are read before the first is used (one LDS round
 //     trip), and the scalar address arithmetic and the loads are issued after the first matrix
@@ -47,7 +51,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-constexpr int kMaxPagesLds = 2048;   // page ids kept in LDS: contexts up to 32768 tokens
+constexpr int kMaxPagesLds = 2048;   // page ids kept in LDS at a time: a window of 32768 tokens that moves with the walk
 
 __device__ inline float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ inline float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
@@ -177,8 +181,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     const int t_begin = item.key_begin / BN;
     const int n_tiles = (kmax + BN - 1) / BN;                   // end of the walk (absolute tile index)
 
-    // page ids of the visible context -> LDS
-    for (int i = tid; i < (kmax + kPageSize - 1) / kPageSize; i += NTHREADS) pg[i] = table[i];
+    // page ids of the visible context -> LDS, a window of kMaxPagesLds pages starting at the first tile's page; the
+    // walk moves the window on when the loads it issues ahead would leave it (once per 32768 keys)
+    const int n_pages = (kmax + kPageSize - 1) / kPageSize;
+    int pg_base = t_begin * (BN / kPageSize);
+    for (int i = tid; i < min(kMaxPagesLds, n_pages - pg_base); i += NTHREADS) pg[i] = table[pg_base + i];
 
     // ---- this lane's query row --------------------------------------------------------------
     const int r_raw = item.row0 + wave * 32 + lq;
@@ -266,7 +273,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int t = min(kt0 + ld_tok[i], kmax - 1);
-            const int page = (ROT || ld_is_v[i]) ? pg[t >> 4] : k_page0 + (t >> 4);
+            const int page = (ROT || ld_is_v[i]) ? pg[(t >> 4) - pg_base] : k_page0 + (t >> 4);
             const uint16_t *base = ld_is_v[i] ? a.v_pool : k_src;
             const uint16_t *src = base + (((int64_t)page * Hkv + g) * kPageSize + (t & 15)) * D + ld_goff[i];
             dma16(src, __builtin_amdgcn_readfirstlane(lds_offset(stage + ld_loff[i])));
@@ -284,7 +291,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int pi = (kt0 + ((wave_u + NW * i) % CHUNKS) * KPC) >> 4;
-            page_v[i] = (ROT || wave_u + NW * i >= CHUNKS) ? pg[pi] : k_page0 + pi;
+            page_v[i] = (ROT || wave_u + NW * i >= CHUNKS) ? pg[pi - pg_base] : k_page0 + pi;
         }
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -347,6 +354,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
         constexpr bool INTERIOR = decltype(interior_tag)::value;
         constexpr bool LIVE = decltype(live_tag)::value;
         const int kt0 = tile * BN;
+        // the loads issued in this iteration look up the pages of tile + NS - 1: move the page-id window when they
+        // would fall outside it.  Every wavefront has left the previous iteration's lookups behind (barrier at its end).
+        if ((tile + NS) * (BN / kPageSize) > pg_base + kMaxPagesLds) {
+            pg_base = tile * (BN / kPageSize);
+            for (int i = tid; i < min(kMaxPagesLds, n_pages - pg_base); i += NTHREADS) pg[i] = table[pg_base + i];
+            __syncthreads();
+        }
         uint8_t *st = ring + (tile % NS) * STAGE;
         uint8_t *st_next = ring + ((tile + 1) % NS) * STAGE;
         const bool compute = LIVE && (INTERIOR || kt0 <= wq_max);

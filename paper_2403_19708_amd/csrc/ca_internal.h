@@ -127,7 +127,6 @@ struct AttnArgs {
 constexpr int kAttnTileRowsMin = 128;   // smallest tile of stacked query rows (4 wavefronts x 32)
 constexpr int kRopeMinRows = 256;       // the kernels read table rows below this whatever the window
 
-hipError_t launch_attn_mfma(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_ref(const AttnArgs &args, hipStream_t stream);
 hipError_t launch_attn_dma(const AttnArgs &args, hipStream_t stream);
 // head_dim 128, 256-row tiles, keys rotated and values transposed once per layer into scratch copies; inside every
@@ -139,7 +138,6 @@ hipError_t launch_attn_combine(const AttnArgs &args, hipStream_t stream);
 // registers instead of matrix-core tiles
 constexpr int kAttnDecodeMaxRows = 2;
 hipError_t launch_attn_decode(const AttnArgs &args, int max_rows, hipStream_t stream);
-constexpr int kAttnDmaMaxPositions = 32768;   // page ids of one conversation are kept in LDS
 constexpr int kAttnMaxParts = 1024;           // shares of split row tiles per batch (sizes the partial-result buffer)
 constexpr int kAttnMaxPartsPerTile = 16;
 constexpr int kAttnMinPartKeys = 256;         // a share is at least this many keys

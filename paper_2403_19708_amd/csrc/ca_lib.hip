@@ -268,8 +268,8 @@ ca_status ca_config_validate(const ca_config *c, char *err, int32_t err_len) {
         set_err(err, err_len, "load_mode (0..2) or attn_variant (0..4) out of range");
         return CA_ERR_INVALID_ARG;
     }
-    if ((c->attn_variant == 2 || c->attn_variant == 4) && c->max_positions > kAttnDmaMaxPositions) {
-        set_err(err, err_len, "attn_variant %d needs max_positions <= %d", c->attn_variant, kAttnDmaMaxPositions);
+    if (c->attn_variant == 3) {
+        set_err(err, err_len, "attn_variant 3 (the register-staged kernel) was removed: the LDS-direct kernel serves every window");
         return CA_ERR_UNSUPPORTED;
     }
     if (c->attn_tile_rows != 0 && c->attn_tile_rows != 128 && c->attn_tile_rows != 256) {
@@ -472,10 +472,9 @@ void ca_destroy(ca_ctx *ctx) {
     delete ctx;
 }
 
-// the kernels that stage K/V through LDS without registers (and the decode kernel) serve windows whose page ids fit in LDS
-static bool direct_variant(const ca_config &c) {
-    return c.attn_variant == 2 || c.attn_variant == 4 || (c.attn_variant == 0 && c.max_positions <= kAttnDmaMaxPositions);
-}
+// every variant but the scalar check kernel stages K/V through LDS without registers (any window: the kernels keep a
+// moving window of page ids in LDS)
+static bool direct_variant(const ca_config &c) { return c.attn_variant != 1; }
 
 static ca_status create_impl(ca_ctx *ctx) {
     const ca_config &c = ctx->cfg;
@@ -1359,7 +1358,7 @@ static ca_status attn_impl(ca_ctx *ctx, int32_t layer, const void *q, const void
     } else if (direct) {
         CA_HIP(ctx, launch_attn_dma(a, stream));
     } else {
-        CA_HIP(ctx, launch_attn_mfma(a, stream));
+        return fail(ctx, CA_ERR_UNSUPPORTED, "ca_cached_prefill_attn: attn_variant %d", c.attn_variant);
     }
     CA_HIP(ctx, prof_end(ctx, iv, stream));
     return CA_OK;

@@ -161,7 +161,7 @@ def variant_config(variant):
     return dict(attn_variant=variant)
 
 
-@pytest.mark.parametrize("variant", [1, 3, 2, 12, 13], ids=["scalar", "staged", "direct", "pipelined", "direct-prerotated"])
+@pytest.mark.parametrize("variant", [1, 2, 12, 13], ids=["scalar", "direct", "pipelined", "direct-prerotated"])
 def test_attention_matches_oracle(case, variant):
     run = GpuRun(case, tier="device", **variant_config(variant))
     try:
@@ -207,7 +207,7 @@ def test_small_batch_splits_keys_over_workgroups(shape, split):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [2, 3, 12, 13], ids=["direct", "staged", "pipelined", "direct-prerotated"])
+@pytest.mark.parametrize("variant", [2, 12, 13], ids=["direct", "pipelined", "direct-prerotated"])
 def test_context_fills_the_largest_window_of_the_direct_kernel(variant):
     """One conversation whose context is exactly 32768 tokens: every entry of the LDS-direct kernel's page
     table is in use, the last tile ends on the window, positions reach 32767 (and the few row tiles of a
@@ -228,7 +228,7 @@ def test_context_fills_the_largest_window_of_the_direct_kernel(variant):
 def test_context_longer_than_one_launch_row_of_pages():
     """A context of more than 32768 pages: the move kernels cap their launch at that many page columns and walk
     the rest in a second trip.  Pool, saved tier and the single new token's attention must come out as for
-    any other length (window 2^20, so the register-staged kernel serves it)."""
+    any other length (window 2^20: the attention kernels' page-id window in LDS moves many times along the way)."""
     hist = 32768 * 16 + 1000
     case = Case([hist], [1], [0], 1, 1, 64, seed=31, window=1 << 20)
     run = GpuRun(case, tier="device")
@@ -246,24 +246,41 @@ def test_context_longer_than_one_launch_row_of_pages():
         run.close()
 
 
-@pytest.mark.parametrize("window", [4096, 65536], ids=["direct-by-default", "staged-beyond-32768"])
-def test_default_variant_follows_the_window(window):
-    """attn_variant 0 takes the LDS-direct kernel while its page-id table holds the window and the
-    register-staged kernel beyond; both must give the oracle's result on the same small case."""
-    case = Case([300, 17], [140, 40], [0, 0], 4, 2, 128, seed=23)
-    run = GpuRun(case, tier="device", max_positions=window)
+@pytest.mark.parametrize("variant", [2, 12], ids=["direct", "pipelined"])
+def test_context_beyond_the_page_id_window_of_the_direct_kernel(variant):
+    """One conversation of 70000 tokens with 150 new ones (window 2^17): the LDS-direct kernel keeps 2048 page ids
+    (32768 tokens) in LDS at a time and has to move that window twice along the walk, in whole and in split row
+    tiles; the pipelined kernel reads scratch pages and needs no table.  A second, short conversation shares the batch."""
+    case = Case([70000, 300], [150, 40], [0, 7], 2, 1, 128, seed=27, window=1 << 17)
+    run = GpuRun(case, tier="device", **variant_config(variant))
     try:
         run.rebase()
         run.run_layer(0)
         run.finish()
         for c in range(case.B):
-            check_contract(run.out_f64(0, c), case.oracle_out(0, c), c)
-            check_tight(run.out_f64(0, c), case.oracle_out(0, c), int(case.n_keep[c]), c)
+            check_contract(run.out_f64(0, c), case.oracle_out(0, c), (variant, c))
+            check_tight(run.out_f64(0, c), case.oracle_out(0, c), int(case.n_keep[c]), (variant, c))
     finally:
         run.close()
 
 
-@pytest.mark.parametrize("variant", [1, 3, 2, 12, 13], ids=["scalar", "staged", "direct", "pipelined", "direct-prerotated"])
+@pytest.mark.parametrize("split", [0, 1], ids=["split", "whole"])
+def test_unsplit_walk_moves_the_page_id_window(split):
+    """The same long context with key splitting switched off (one workgroup walks all 1100 tiles and moves the page-id
+    window along the way) and on."""
+    case = Case([70000], [33], [0], 1, 1, 64, seed=28, window=1 << 17, style=1)
+    run = GpuRun(case, tier="device", attn_variant=2, attn_split=split)
+    try:
+        run.rebase()
+        run.run_layer(0)
+        run.finish()
+        check_contract(run.out_f64(0, 0), case.oracle_out(0, 0), split)
+        check_tight(run.out_f64(0, 0), case.oracle_out(0, 0), int(case.n_keep[0]), split)
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("variant", [1, 2, 12, 13], ids=["scalar", "direct", "pipelined", "direct-prerotated"])
 def test_attention_peaky_softmax(variant):
     """Queries scaled x6: a handful of keys dominate each row and outputs are O(1), so a wrong key,
     a wrong mask edge or a wrong position cannot hide under the tolerance.  Scores grow with the
@@ -305,7 +322,7 @@ def test_attention_peaky_softmax(variant):
         run.close()
 
 
-@pytest.mark.parametrize("variant", [3, 2, 12, 13], ids=["staged", "direct", "pipelined", "direct-prerotated"])
+@pytest.mark.parametrize("variant", [2, 12, 13], ids=["direct", "pipelined", "direct-prerotated"])
 def test_attention_peaky_softmax_against_the_plain_oracle(variant):
     """Queries scaled x2: rows rest on a few keys and outputs are O(1), and at this scale the bf16 rounding of the
     rotated Q/K still leaves the kernels inside the contract against the oracle as it stands (no rounding point

@@ -25,7 +25,7 @@ def draw_case(seed):
     new = np.where(rng.random(B) < 0.3, rng.integers(1, 4, B), rng.integers(1, 300, B)).astype(np.int32)
     keep = np.array([int(rng.integers(0, h + 1)) if rng.random() < 0.6 else 0 for h in hist], np.int32)
     knobs = dict(attn_split=int(rng.integers(0, 2)), attn_prerotate=int(rng.choice([0, 1, 2])), attn_schedule=int(rng.integers(0, 2)),
-                 attn_variant=int(rng.choice([0, 0, 2, 3])), attn_tile_rows=int(rng.choice([0, 0, 128, 256])))
+                 attn_variant=int(rng.choice([0, 0, 2])), attn_tile_rows=int(rng.choice([0, 0, 128, 256])))
     case = Case(hist, new, keep, Hkv * G, Hkv, D, seed=2000 + seed, style=style, window=2048)
     return case, knobs
 

@@ -63,8 +63,7 @@ def test_config_default_and_struct_layout(lib):
     (dict(attn_variant=7), "CA_ERR_INVALID_ARG"),
     (dict(attn_split=2), "CA_ERR_INVALID_ARG"),
     (dict(attn_prerotate=3), "CA_ERR_INVALID_ARG"),
-    (dict(attn_variant=2, max_positions=65536), "CA_ERR_UNSUPPORTED"),
-    (dict(attn_variant=4, max_positions=65536), "CA_ERR_UNSUPPORTED"),
+    (dict(attn_variant=3), "CA_ERR_UNSUPPORTED"),
     (dict(attn_variant=5), "CA_ERR_INVALID_ARG"),
 ])
 def test_config_validation(lib, kw, status):
