@@ -69,7 +69,8 @@ def parse():
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
     ap.add_argument("--load-mode", type=int, default=0, help="library load_mode (0 staged copies for a host tier, 2 kernels read the tier in place)")
     ap.add_argument("--save-mode", type=int, default=0)
-    ap.add_argument("--depth", type=int, default=2, help="staging slots of the read stream (pipeline_depth) in the headline leg")
+    ap.add_argument("--depth", type=int, default=4, help="staging slots of the read stream (pipeline_depth) in the headline leg")
+    ap.add_argument("--timeline-file", type=str, default="", help="write the per-interval timeline of the instrumented step here")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging only; marks the result invalid)")
     return ap.parse_args()
 
@@ -257,7 +258,7 @@ class Job:
             self.compute_layer(ctx, l, src_k, src_v, stream)
         ctx.join(stream)
 
-    def timed(self, ctx, src_k, src_v, stream, warmup, steps, tag, kinds=None):
+    def timed(self, ctx, src_k, src_v, stream, warmup, steps, tag, kinds=None, timeline=False):
         """kinds: which of the library's kernels/copies are bracketed by HIP events during the timed steps
         (None = all; the events cost a few per cent of a step made of short kernels)"""
         torch, ca = self.torch, self.ca
@@ -273,7 +274,10 @@ class Job:
         ctx.sync(); torch.cuda.synchronize()
         dt = time.perf_counter() - t
         ctx.profile_enable(False)
+        tl = ctx.profile_timeline() if timeline else None
         prof = {k: ctx.profile_read(k) for k in ca.Context.PROFILE_KINDS}
+        if timeline:
+            prof["timeline"] = tl
         log(f"[bench] {tag}: {steps} steps in {dt * 1e3:.1f} ms")
         return dt, prof
 
@@ -401,6 +405,63 @@ def pipeline_figures(job, dt, steps, prof):
             note="Section 3.2.1 with attention as the only compute: loading a layer takes longer than computing it, so the "
                  "pipeline is bound by the host link and the formula asks for a read buffer of nearly the whole stack"),
     )
+
+
+def _union(iv):
+    """sorted disjoint union of intervals"""
+    out = []
+    for a, b in sorted(iv):
+        if out and a <= out[-1][1]:
+            out[-1][1] = max(out[-1][1], b)
+        else:
+            out.append([a, b])
+    return out
+
+
+def _common(u, v):
+    """total length of the intersection of two disjoint sorted interval lists"""
+    i = j = 0
+    tot = 0.0
+    while i < len(u) and j < len(v):
+        lo, hi = max(u[i][0], v[j][0]), min(u[i][1], v[j][1])
+        if hi > lo:
+            tot += hi - lo
+        if u[i][1] < v[j][1]:
+            i += 1
+        else:
+            j += 1
+    return tot
+
+
+def timeline_figures(tl, path=None):
+    """Where the time of one step with a host tier goes, from the library's own event pairs around every copy
+    batch and kernel (all on one clock): how much of the attention runs while the read stream is copying, and
+    what is left uncovered at the head and the tail of the step."""
+    by = {}
+    for kind, a, b in tl:
+        by.setdefault(kind, []).append((a, b))
+    length = lambda u: sum(b - a for a, b in u)
+    cin, att = _union(by.get("copy_in", [])), _union(by.get("attn", []))
+    comp = _union(by.get("attn", []) + by.get("unpack", []) + by.get("append", []))
+    cout = _union(by.get("copy_out", []))
+    t0, t1 = min(a for _, a, _ in tl), max(b for _, _, b in tl)
+    res = dict(span_ms=t1 - t0, copy_in_busy_ms=length(cin), attn_busy_ms=length(att), compute_busy_ms=length(comp),
+               copy_out_busy_ms=length(cout), attn_under_copy_in_ms=_common(att, cin), copy_in_under_compute_ms=_common(cin, comp),
+               head_before_first_attn_ms=(att[0][0] - t0) if att else None,
+               tail_after_last_copy_in_ms=(t1 - cin[-1][1]) if cin else None,
+               read_stream_idle_ms=(t1 - t0) - length(cin),
+               note="one step with every copy batch and kernel bracketed by events; head = the first layer's load, which nothing can "
+                    "hide; tail = the last layer's unpack, attention, save and write-back after the read stream has finished")
+    if att:
+        res["attn_under_copy_in_frac"] = res["attn_under_copy_in_ms"] / res["attn_busy_ms"]
+    if path:
+        with open(path, "w") as f:
+            f.write("# kind index start_ms stop_ms (index = order within the kind = layer for copy_in, attn, copy_out)\n")
+            seen = {}
+            for kind, a, b in tl:
+                i = seen.get(kind, 0); seen[kind] = i + 1
+                f.write(f"{kind} {i} {a:.4f} {b:.4f}\n")
+    return res
 
 
 def depth_sweep(torch, ca, job, host_k, host_v, stream, depths, args):
@@ -647,17 +708,18 @@ def main():
     if want_hbm:
         job.make_device_tier()
     log(f"[bench] device tensors ready after {time.time() - t_begin:.0f}s, {torch.cuda.memory_allocated() / 2**30:.1f} GiB on device")
-    pinned_ok = True
+    pinned_ok = args.tier == "pinned" or not args.no_sweeps
     host_k = host_v = None
-    try:
-        job.make_pinned_tier()
-        host_k, host_v = job.tier_ptrs(job.pin_tier[0]), job.tier_ptrs(job.pin_tier[1])
-        log(f"[bench] pinned tier ready after {time.time() - t_begin:.0f}s")
-    except Exception as e:
-        pinned_ok = False
-        log(f"[bench] pinned tier failed: {e!r}")
-        if args.tier == "pinned":
-            raise
+    if pinned_ok:
+        try:
+            job.make_pinned_tier()
+            host_k, host_v = job.tier_ptrs(job.pin_tier[0]), job.tier_ptrs(job.pin_tier[1])
+            log(f"[bench] pinned tier ready after {time.time() - t_begin:.0f}s")
+        except Exception as e:
+            pinned_ok = False
+            log(f"[bench] pinned tier failed: {e!r}")
+            if args.tier == "pinned":
+                raise
     dev_k = dev_v = None
     if want_hbm:
         dev_k, dev_v = job.tier_ptrs(job.dev_tier[0]), job.tier_ptrs(job.dev_tier[1])
@@ -686,8 +748,11 @@ def main():
             log("[bench] PARITY FAILED: the numbers below are not valid")
 
     # every kernel bracketed, same tier: in-step durations of the move kernels
-    dt_i, prof_i = job.timed(ctx, src_k, src_v, stream, 0, 1, f"{tier_name} tier, every kernel timed")
+    dt_i, prof_i = job.timed(ctx, src_k, src_v, stream, 0, 1, f"{tier_name} tier, every kernel timed", timeline=True)
     kv_move = job.move_figures(prof_i)
+    if pipeline is not None and prof_i.get("timeline"):
+        pipeline["timeline"] = timeline_figures(prof_i["timeline"], args.timeline_file or None)
+        pipeline["timeline"]["ms_step_instrumented"] = dt_i * 1e3
 
     # the dominant kernel of the step by GPU time: the attention call
     attn_kernel = "attn_dma_kernel"
@@ -752,7 +817,7 @@ def main():
     sweep = None
     if not args.no_sweeps and pinned_ok:
         try:
-            sweep = depth_sweep(torch, ca, job, host_k, host_v, stream, [1, 2, 4], args)
+            sweep = depth_sweep(torch, ca, job, host_k, host_v, stream, [1, 2, 4, 8], args)
         except Exception as e:
             log(f"[bench] depth sweep failed: {e!r}")
             sweep = dict(error=repr(e))

@@ -275,6 +275,15 @@ ca_status ca_join(ca_ctx *ctx, void *stream);
 ca_status ca_profile_enable(ca_ctx *ctx, int32_t on);
 ca_status ca_profile_read(ca_ctx *ctx, int32_t kind, double *total_ms, int64_t *count);
 
+/* The recorded intervals that have not been read yet, in the order they were queued, without
+ * forgetting them: kinds[i] as above, start_ms[i] and stop_ms[i] on one clock whose zero is the
+ * start of the first interval still held (intervals of different streams are comparable, so the
+ * overlap of copies and kernels can be read off). Host arrays of `capacity` entries each;
+ * *count receives the number held, of which the first min(*count, capacity) are written.
+ * Synchronises the device.                                                                   */
+ca_status ca_profile_timeline(ca_ctx *ctx, int32_t *kinds, double *start_ms, double *stop_ms,
+                              int64_t capacity, int64_t *count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ SYMBOLS = ["ca_config_default", "ca_config_validate", "ca_batch_validate", "ca_c
            "ca_last_error", "ca_status_string", "ca_truncate_plan", "ca_truncate_plan_sinks", "ca_rope_rebase", "ca_rebase_read",
            "ca_kv_load_layer", "ca_kv_append_layer", "ca_cached_prefill_attn", "ca_cached_prefill_attn_static",
            "ca_kv_save_layer", "ca_kv_append_save_layer",
-           "ca_sync", "ca_join", "ca_profile_enable", "ca_profile_read"]
+           "ca_sync", "ca_join", "ca_profile_enable", "ca_profile_read", "ca_profile_timeline"]
 
 
 class CaError(RuntimeError):
@@ -110,6 +110,8 @@ def load_library():
     lib.ca_profile_enable.restype = C.c_int
     lib.ca_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), i64p]
     lib.ca_profile_read.restype = C.c_int
+    lib.ca_profile_timeline.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int64, i64p]
+    lib.ca_profile_timeline.restype = C.c_int
     _lib = lib
     return lib
 
@@ -370,3 +372,15 @@ class Context:
         ms, n = C.c_double(0.0), C.c_int64(0)
         self._check(self._lib.ca_profile_read(self._h, k, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+    def profile_timeline(self):
+        """[(kind name, start ms, stop ms)] of the intervals not read yet, on one clock (zero = the first one's start)."""
+        n = C.c_int64(0)
+        self._check(self._lib.ca_profile_timeline(self._h, None, None, None, 0, C.byref(n)))
+        cap = n.value
+        if cap == 0:
+            return []
+        kinds, t0, t1 = (C.c_int32 * cap)(), (C.c_double * cap)(), (C.c_double * cap)()
+        self._check(self._lib.ca_profile_timeline(self._h, kinds, t0, t1, cap, C.byref(n)))
+        names = {v: k for k, v in self.PROFILE_KINDS.items()}
+        return [(names[kinds[i]], t0[i], t1[i]) for i in range(min(cap, n.value))]

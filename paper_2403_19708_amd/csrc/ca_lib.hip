@@ -33,7 +33,7 @@ struct ca_ctx {
     // staging ring: `depth` slots for loads, `depth` for saves; slot = [K tokens | V tokens]
     uint8_t *load_slots = nullptr, *save_slots = nullptr;
     size_t slot_bytes = 0, half_slot_bytes = 0;
-    std::vector<hipEvent_t> ev_slot_copied, ev_slot_free;  // per load slot
+    std::vector<hipEvent_t> ev_slot_copied, ev_slot_copied2, ev_slot_free;  // per load slot
     std::vector<uint8_t> slot_used;
     int64_t load_count = 0, save_count = 0;
     float2 *rope = nullptr;
@@ -450,6 +450,7 @@ void ca_destroy(ca_ctx *ctx) {
     if (ctx->s_unpack) (void)hipStreamSynchronize(ctx->s_unpack);
     if (ctx->s_save) (void)hipStreamSynchronize(ctx->s_save);
     for (auto e : ctx->ev_slot_copied) if (e) (void)hipEventDestroy(e);
+    for (auto e : ctx->ev_slot_copied2) if (e) (void)hipEventDestroy(e);
     for (auto e : ctx->ev_slot_free) if (e) (void)hipEventDestroy(e);
     for (auto e : ctx->ev_ready) if (e) (void)hipEventDestroy(e);
     if (ctx->ev_meta_copied) (void)hipEventDestroy(ctx->ev_meta_copied);
@@ -491,10 +492,12 @@ static ca_status create_impl(ca_ctx *ctx) {
     CA_HIP(ctx, hipMalloc((void **)&ctx->load_slots, ctx->slot_bytes * depth));
     CA_HIP(ctx, hipMalloc((void **)&ctx->save_slots, ctx->slot_bytes * depth));
     ctx->ev_slot_copied.assign(depth, nullptr);
+    ctx->ev_slot_copied2.assign(depth, nullptr);
     ctx->ev_slot_free.assign(depth, nullptr);
     ctx->slot_used.assign(depth, 0);
     for (int i = 0; i < depth; ++i) {
         CA_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_slot_copied[i], hipEventDisableTiming));
+        CA_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_slot_copied2[i], hipEventDisableTiming));
         CA_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_slot_free[i], hipEventDisableTiming));
     }
     ctx->ev_ready.assign(c.n_layers, nullptr);
@@ -1017,7 +1020,11 @@ ca_status ca_kv_load_layer(ca_ctx *ctx, int32_t layer, const void *const *src_k,
         const int slot = (int)(ctx->load_count % c.pipeline_depth);
         uint8_t *sk = ctx->load_slots + (size_t)slot * ctx->slot_bytes;
         uint8_t *sv = sk + ctx->half_slot_bytes;
-        // the slot is free again once the unpack that last read it has finished
+        // The K half is copied on the copy stream and the V half on the unpack stream, ahead of the kernel that needs
+        // both: two copy queues keep the host link busier than one (each fills the gaps between the other's
+        // per-conversation copies), and a stream of its own for the second queue would be one more than the hardware
+        // queues a process has, which makes unrelated streams wait for each other.
+        // the slot is free again once the unpack that last read it has finished (the unpack stream is behind it anyway)
         if (ctx->slot_used[slot]) CA_HIP(ctx, hipStreamWaitEvent(ctx->s_copy, ctx->ev_slot_free[slot], 0));
         int iv_copy;
         CA_HIP(ctx, prof_begin(ctx, kProfCopyIn, ctx->s_copy, &iv_copy));
@@ -1030,10 +1037,15 @@ ca_status ca_kv_load_layer(ca_ctx *ctx, int32_t layer, const void *const *src_k,
                 const size_t src_off = (size_t)ctx->keep_rng[r].first * rb;
                 const size_t bytes = (size_t)(ctx->keep_rng[r].second - ctx->keep_rng[r].first) * rb;
                 CA_HIP(ctx, hipMemcpyAsync(sk + dst_off, (const uint8_t *)src_k[i] + src_off, bytes, hipMemcpyDefault, ctx->s_copy));
-                CA_HIP(ctx, hipMemcpyAsync(sv + dst_off, (const uint8_t *)src_v[i] + src_off, bytes, hipMemcpyDefault, ctx->s_copy));
+                CA_HIP(ctx, hipMemcpyAsync(sv + dst_off, (const uint8_t *)src_v[i] + src_off, bytes, hipMemcpyDefault, ctx->s_unpack));
                 dst_off += bytes;
             }
             segs.push_back({sk, sv, ctx->cu_n[i], 0, (int32_t)n, i});
+        }
+        if (iv_copy >= 0) {
+            // a timed copy-in ends when both halves have landed (only then do the two queues meet once per layer)
+            CA_HIP(ctx, hipEventRecord(ctx->ev_slot_copied2[slot], ctx->s_unpack));
+            CA_HIP(ctx, hipStreamWaitEvent(ctx->s_copy, ctx->ev_slot_copied2[slot], 0));
         }
         CA_HIP(ctx, prof_end(ctx, iv_copy, ctx->s_copy));
         CA_HIP(ctx, hipEventRecord(ctx->ev_slot_copied[slot], ctx->s_copy));
@@ -1414,6 +1426,26 @@ ca_status ca_profile_read(ca_ctx *ctx, int32_t kind, double *total_ms, int64_t *
     ctx->intervals.swap(keep);
     *total_ms = sum;
     *count = n;
+    return CA_OK;
+}
+
+ca_status ca_profile_timeline(ca_ctx *ctx, int32_t *kinds, double *start_ms, double *stop_ms, int64_t capacity,
+                              int64_t *count) {
+    if (!ctx || !count || capacity < 0) return CA_ERR_INVALID_ARG;
+    if (capacity > 0 && (!kinds || !start_ms || !stop_ms)) return fail(ctx, CA_ERR_INVALID_ARG, "ca_profile_timeline: null array");
+    CA_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    CA_HIP(ctx, hipDeviceSynchronize());
+    *count = (int64_t)ctx->intervals.size();
+    const int64_t n = std::min<int64_t>(*count, capacity);
+    for (int64_t i = 0; i < n; ++i) {
+        const auto &iv = ctx->intervals[(size_t)i];
+        float a = 0.f, b = 0.f;
+        if (i > 0) CA_HIP(ctx, hipEventElapsedTime(&a, ctx->intervals[0].start, iv.start));
+        CA_HIP(ctx, hipEventElapsedTime(&b, iv.start, iv.stop));
+        kinds[i] = iv.kind;
+        start_ms[i] = a;
+        stop_ms[i] = (double)a + b;
+    }
     return CA_OK;
 }
 

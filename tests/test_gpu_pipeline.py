@@ -257,3 +257,48 @@ def test_config2_full_size_stack_on_the_pinned_tier_every_output():
         print(f"config 2, three layers, every output: worst max-abs {worst:.2e}")
     finally:
         run.close()
+
+
+def test_event_timeline_respects_the_order_the_streams_must_keep():
+    """The library's own event pairs, read on one clock: per layer the attention starts after that layer's
+    unpack has ended, the unpack after its copy-in, the write-back after the attention; reading the timeline
+    does not consume the intervals."""
+    case = Case([300, 64, 0, 777], [40, 130, 9, 257], [20, 0, 0, 300], 4, 2, 128, seed=52, n_layers=5, window=1024)
+    run = GpuRun(case, tier="pinned", pipeline_depth=2, load_mode=0)
+    try:
+        stream = torch.cuda.Stream()
+        run.ctx.profile_enable(True)
+        with torch.cuda.stream(stream):
+            run.rebase(stream)
+            for l in range(case.n_layers):
+                run.load(l)
+            for l in range(case.n_layers):
+                run.append(l, stream)
+                run.attn(l, stream)
+                run.save(l, after_stream=stream)
+        run.finish()
+        run.ctx.profile_enable(False)
+        tl = run.ctx.profile_timeline()
+        assert tl == run.ctx.profile_timeline()
+        per = {}
+        for kind, a, b in tl:
+            assert b >= a >= 0.0
+            per.setdefault(kind, []).append((a, b))
+        L = case.n_layers
+        for kind in ("copy_in", "attn", "copy_out"):
+            assert len(per[kind]) == L, (kind, len(per[kind]))
+        for kind in per:
+            ms, n = run.ctx.profile_read(kind)
+            assert n == len(per[kind])
+            assert abs(ms - sum(b - a for a, b in per[kind])) <= 1e-3 * max(1.0, ms)
+        assert run.ctx.profile_timeline() == []
+        n_unpack = len(per["unpack"]) // L
+        eps = 2e-3      # event timestamps of different streams: allow two microseconds
+        for l in range(L):
+            unpack_end = max(b for _, b in per["unpack"][l * n_unpack:(l + 1) * n_unpack])
+            unpack_begin = min(a for a, _ in per["unpack"][l * n_unpack:(l + 1) * n_unpack])
+            assert unpack_begin >= per["copy_in"][l][1] - eps, l
+            assert per["attn"][l][0] >= unpack_end - eps, l
+            assert per["copy_out"][l][0] >= per["attn"][l][1] - eps, l
+    finally:
+        run.close()
