@@ -407,6 +407,21 @@ def pipeline_figures(job, dt, steps, prof):
     )
 
 
+def link_probe(torch):
+    """the host link by itself: one 320 MiB copy from pinned host memory to the device, best of five"""
+    n = 320 * 1024 * 1024 // 2
+    h = torch.empty(n, dtype=torch.bfloat16, pin_memory=True)
+    d = torch.empty(n, dtype=torch.bfloat16, device="cuda:0")
+    d.copy_(h, non_blocking=True); torch.cuda.synchronize()
+    best = 0.0
+    for _ in range(5):
+        t = time.perf_counter()
+        d.copy_(h, non_blocking=True); torch.cuda.synchronize()
+        best = max(best, n * 2 / (time.perf_counter() - t) / 1e9)
+    del h, d
+    return best
+
+
 def _union(iv):
     """sorted disjoint union of intervals"""
     out = []
@@ -740,6 +755,15 @@ def main():
     att_us_live = prof["attn"][0] / prof["attn"][1] * 1e3
     attn_live = job.attn_figures(att_us_live)
     pipeline = pipeline_figures(job, dt, args.steps, prof) if args.tier == "pinned" else None
+    if pipeline is not None:
+        # the step is bound by the read stream, so what bounds the headline value is the host link, not a kernel
+        peak = link_probe(torch)
+        step_gbs = L * job.link_in_bytes / (dt / args.steps) / 1e9
+        pipeline["link"] = dict(step_gbs=step_gbs, single_copy_gbs=peak, frac_of_single_copy=step_gbs / peak,
+                                pcie5_x16_gbs=63.0, frac_of_pcie5_x16=step_gbs / 63.0,
+                                note="step_gbs = tier bytes read per step / step time (everything else hidden or not); "
+                                     "single_copy_gbs = one 320 MiB pinned-to-device copy on an idle GPU, measured in this run")
+        log(f"[bench] host link: {step_gbs:.1f} GB/s over the whole step, {peak:.1f} GB/s for one large copy alone")
 
     parity = None
     if not args.no_check and job.layer0:

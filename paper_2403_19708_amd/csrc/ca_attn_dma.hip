@@ -6,7 +6,10 @@
 // staged K/V tile), walking key tiles of BN with an online softmax.  v_mfma_f32_32x32x16_bf16 in the transposed
 // formulation S^T = K Q^T, O^T += V^T P^T: in the C layout a lane owns one query column, so row maxima and sums are
 // in-lane plus one exchange with lane ^ 32, and the C registers of S^T, converted to bf16, ARE the B operand of the
-// second product.  The reference maximum is raised lazily (a wave-uniform branch, rare after the first tile).
+// second product.  The softmax scale and log2(e) are folded into the rotated query before it is rounded to bf16 and the
+// running reference maximum enters the score product as its initial accumulator (-m), so the exponent's argument comes
+// straight out of the matrix instruction.  The reference maximum is raised lazily (a wave-uniform branch, rare after
+// the first tile).
 // K/V tiles travel HBM -> LDS without passing through registers:
 //
 //   * global_load_lds (16 bytes per lane, written to LDS at base + lane*16) fills a ring of 4 tile
@@ -111,18 +114,19 @@ __device__ inline void load_cs(const float2 *__restrict__ rope, int pos, int pie
 }
 
 // one dword (2 elements) of each of the two 16-byte pieces a (dims d0..) and b (dims d0 + D/2..)
+// (f = a factor applied to the rotated values before they are rounded)
 template <int STYLE>
-__device__ inline void rotate_dword(uint32_t &pa, uint32_t &pb, const float2 (&cs)[8], int w) {
+__device__ inline void rotate_dword(uint32_t &pa, uint32_t &pb, const float2 (&cs)[8], int w, float f = 1.0f) {
     const float a0 = bf_lo(pa), a1 = bf_hi(pa);
     const float b0 = bf_lo(pb), b1 = bf_hi(pb);
     if (STYLE == 0) {
         const float2 c0 = cs[2 * w], c1 = cs[2 * w + 1];
-        pa = pack_bf16(a0 * c0.x - b0 * c0.y, a1 * c1.x - b1 * c1.y);
-        pb = pack_bf16(b0 * c0.x + a0 * c0.y, b1 * c1.x + a1 * c1.y);
+        pa = pack_bf16((a0 * c0.x - b0 * c0.y) * f, (a1 * c1.x - b1 * c1.y) * f);
+        pb = pack_bf16((b0 * c0.x + a0 * c0.y) * f, (b1 * c1.x + a1 * c1.y) * f);
     } else {
         const float2 ca_ = cs[w], cb_ = cs[4 + w];
-        pa = pack_bf16(a0 * ca_.x - a1 * ca_.y, a1 * ca_.x + a0 * ca_.y);
-        pb = pack_bf16(b0 * cb_.x - b1 * cb_.y, b1 * cb_.x + b0 * cb_.y);
+        pa = pack_bf16((a0 * ca_.x - a1 * ca_.y) * f, (a1 * ca_.x + a0 * ca_.y) * f);
+        pb = pack_bf16((b0 * cb_.x - b1 * cb_.y) * f, (b1 * cb_.x + b0 * cb_.y) * f);
     }
 }
 
@@ -134,8 +138,9 @@ __device__ inline void rotate_dword(uint32_t &pa, uint32_t &pb, const float2 (&c
 // dense pages numbered per conversation; used when many row tiles share the keys of a (conversation, kv head)
 // and rotating them once beats rotating them in every tile.
 // NS = LDS stages of the tile ring: the loads of tile T+NS-1 go out in iteration T.
-template <int D, int STYLE, int NW, int BN, bool ROT = true, int NS = 4>
-__global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
+// PGW = page ids kept in LDS at a time, OCC = wavefronts per SIMD the register budget is cut for.
+template <int D, int STYLE, int NW, int BN, bool ROT = true, int NS = 4, int PGW = kMaxPagesLds, int OCC = 2>
+__global__ __launch_bounds__(64 * NW, OCC) void attn_dma_kernel(AttnArgs a) {
     static_assert(ROT ? NS >= 4 : NS >= 2, "the in-place rotary pass needs a tile landed one iteration early");
     constexpr int NTHREADS = 64 * NW;
     constexpr int MB = BN / 32;              // 32-key blocks of S^T per tile
@@ -152,10 +157,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     constexpr int NI = 2 * CHUNKS / NW;      // load instructions per thread and tile (K and V)
     constexpr int ROT_TASKS = BN * PPR / 2;  // (key, piece pair) tasks of the rotary pass
     static_assert(2 * CHUNKS % NW == 0, "chunks divide evenly over the wavefronts");
-    static_assert((NW == 8 ? 1 : 2) * (NS * STAGE + kMaxPagesLds * 4) <= 160 * 1024, "LDS budget");
+    static_assert((NW == 8 ? 1 : OCC) * (NS * STAGE + PGW * 4) <= 160 * 1024, "LDS budget");
+    // loads that may still be in flight at the end of an interior iteration: with the rotary pass tile+2 must have
+    // landed (it is rotated next), without it only tile+1
+    constexpr int FLY = ROT ? (NS > 3 ? NI : 0) : (NS - 2) * NI;
 
     __shared__ __attribute__((aligned(16))) uint8_t ring[NS * STAGE];
-    __shared__ int32_t pg[kMaxPagesLds];
+    __shared__ int32_t pg[PGW];
 
     const WorkItem item = a.items[blockIdx.x];
     if (item.seq < 0) return;
@@ -185,7 +193,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     // walk moves the window on when the loads it issues ahead would leave it (once per 32768 keys)
     const int n_pages = (kmax + kPageSize - 1) / kPageSize;
     int pg_base = t_begin * (BN / kPageSize);
-    for (int i = tid; i < min(kMaxPagesLds, n_pages - pg_base); i += NTHREADS) pg[i] = table[pg_base + i];
+    for (int i = tid; i < min(PGW, n_pages - pg_base); i += NTHREADS) pg[i] = table[pg_base + i];
 
     // ---- this lane's query row --------------------------------------------------------------
     const int r_raw = item.row0 + wave * 32 + lq;
@@ -200,6 +208,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     const int wq_min = n + wr_first / G;
     const int wq_max = n + wr_last / G;
 
+    // The softmax scale and log2(e) are folded into the rotated query before it is rounded to bf16, so the scores
+    // come out of the matrix cores in the units of the base-2 exponent.
+    const float cscale = a.softmax_scale * 1.4426950408889634f;
     bf16x8 Qf[KSTEPS];
     {
         const uint16_t *qrow = a.q + ((int64_t)(q0 + j) * a.n_q_heads + head) * D;
@@ -212,7 +223,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
             load_cs<D, STYLE>(a.rope, qpos, piece, cs);
             uint32_t *px = reinterpret_cast<uint32_t *>(&x), *py = reinterpret_cast<uint32_t *>(&y);
 #pragma unroll
-            for (int w = 0; w < 4; ++w) rotate_dword<STYLE>(px[w], py[w], cs, w);
+            for (int w = 0; w < 4; ++w) rotate_dword<STYLE>(px[w], py[w], cs, w, cscale);
             Qf[ks] = __builtin_bit_cast(bf16x8, x);
             Qf[ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, y);
         }
@@ -333,9 +344,15 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
     for (int db = 0; db < DBLKS; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[db][i] = 0.f;
+    // m_run = reference maximum of this lane's query row in exponent units (-inf: no key seen yet); neg_m holds
+    // -m_run (0 while there is none) in the C layout and is the accumulator input of the first matrix instruction
+    // of every tile, so the scores arrive already relative to the reference and the common path of the softmax
+    // is exp2 of the accumulator, with no subtraction per element
     float m_run = -INFINITY;
     float l_run = 0.f;
-    const float cscale = a.softmax_scale * 1.4426950408889634f;
+    f32x16 neg_m;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) neg_m[i] = 0.f;
     const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
     // ---- prologue ---------------------------------------------------------------------------------------
@@ -356,9 +373,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
         const int kt0 = tile * BN;
         // the loads issued in this iteration look up the pages of tile + NS - 1: move the page-id window when they
         // would fall outside it.  Every wavefront has left the previous iteration's lookups behind (barrier at its end).
-        if ((tile + NS) * (BN / kPageSize) > pg_base + kMaxPagesLds) {
+        if ((tile + NS) * (BN / kPageSize) > pg_base + PGW) {
             pg_base = tile * (BN / kPageSize);
-            for (int i = tid; i < min(kMaxPagesLds, n_pages - pg_base); i += NTHREADS) pg[i] = table[pg_base + i];
+            for (int i = tid; i < min(PGW, n_pages - pg_base); i += NTHREADS) pg[i] = table[pg_base + i];
             __syncthreads();
         }
         uint8_t *st = ring + (tile % NS) * STAGE;
@@ -376,15 +393,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
         f32x16 S[MB];
         if (compute) {
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) S[mb][i] = 0.f;
-#pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
                     const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + k_rd[mb] + ks * (2 * KPC * 16));
-                    S[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[ks], S[mb], 0, 0, 0);
+                    S[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[ks], ks == 0 ? neg_m : S[mb], 0, 0, 0);
                 }
                 if (INTERIOR && ks == 0) {
                     __builtin_amdgcn_sched_barrier(0);
@@ -417,21 +430,30 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
                 const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
                 mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
             }
-            const bool raise = (mx - m_run) * cscale > 8.0f;
+            // mx is relative to the reference.  The reference follows the maximum lazily: it moves when a row sees its
+            // first key (whatever the value) or when a score exceeds it by more than 8 (probabilities up to 2^8 are
+            // harmless in fp32 and bf16).  A row whose keys so far were all masked (possible when the keys of a row
+            // tile are split) has mx = -inf and stays without a reference: its probabilities are exp2(-inf) = 0.
+            const bool unseen = m_run == -INFINITY;
+            const bool raise = mx > -INFINITY && (unseen || mx > 8.0f);
             if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-                const float m_new = raise ? mx : m_run;
-                // (a row that has not seen a key yet keeps its -inf reference and must not turn 0 * exp2(nan) into nan)
-                const float alpha = raise ? __builtin_amdgcn_exp2f((m_run - m_new) * cscale) : 1.0f;
-                m_run = m_new;
+                const float delta = raise ? mx : 0.f;
+                // (a first reference rescales nothing: the sums are still zero, and exp2(-delta) could overflow)
+                const float alpha = (raise && !unseen) ? __builtin_amdgcn_exp2f(-delta) : 1.0f;
+                if (raise) m_run = (unseen ? 0.f : m_run) + mx;
                 l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < DBLKS; ++db)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) O[db][i] *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) S[mb][i] -= delta;
+                const float nm = (m_run == -INFINITY) ? 0.f : -m_run;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) neg_m[i] = nm;
             }
-            // masked tiles: a row that has seen no key so far (possible when the keys are split) has S = -inf
-            // throughout and must get probabilities 0, not exp2(-inf + inf)
-            const float mc = (!INTERIOR && m_run == -INFINITY) ? 0.f : m_run * cscale;
             float psum = 0.f;
 #pragma unroll
             for (int ks2 = 0; ks2 < KS2; ++ks2) {
@@ -439,8 +461,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
                 uint32_t pk[4];
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
-                    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][8 * kk2 + 2 * w], cscale, -mc));
-                    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mb][8 * kk2 + 2 * w + 1], cscale, -mc));
+                    const float p0 = __builtin_amdgcn_exp2f(S[mb][8 * kk2 + 2 * w]);
+                    const float p1 = __builtin_amdgcn_exp2f(S[mb][8 * kk2 + 2 * w + 1]);
                     pk[w] = pack_bf16(p0, p1);
                     // the denominator sums the rounded probabilities, the very values the second product uses
                     psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[w]), ones2, psum, false);
@@ -464,7 +486,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
 
         // tile+2 must have landed before anyone rotates it in the next iteration; the loads of tile+3
         // (issued at the top of this iteration) may stay in flight
-        if (INTERIOR && NS > 3) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }
+        if (INTERIOR) { CA_WAIT_VMCNT(FLY); } else { CA_WAIT_VMCNT(0); }
         __syncthreads();
     };
 
@@ -496,7 +518,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_dma_kernel(AttnArgs a) {
                     *reinterpret_cast<float4 *>(prow + d) = make_float4(O[db][4 * i4], O[db][4 * i4 + 1], O[db][4 * i4 + 2], O[db][4 * i4 + 3]);
                 }
             if (half == 0) {
-                base[(int64_t)a.tile_rows * D + rt] = m_run;
+                base[(int64_t)a.tile_rows * D + rt] = m_run / cscale;      // combine_kernel takes it in score units
                 base[(int64_t)a.tile_rows * (D + 1) + rt] = l_all;
             }
         }

@@ -305,13 +305,10 @@ def test_attention_peaky_softmax(variant):
                 Kr = np.array([[oracle.rope(K[t, g], t) for g in range(K.shape[1])] for t in range(K.shape[0])])
                 Qr = np.array([[oracle.rope(Q[j, h], n + j) for h in range(Q.shape[1])] for j in range(ln)])
                 Kr = w(f32_to_bf16_bits(Kr.astype(np.float32)))
-                if variant == 12:
-                    # this kernel folds softmax scale * log2(e) into the rotated query before rounding it; dividing
-                    # the rounded value by the same factor gives the oracle exactly the scores the kernel forms
-                    fold = np.float32(1.0 / np.sqrt(case.head_dim)) * np.float32(1.4426950408889634)
-                    Qr = w(f32_to_bf16_bits(Qr.astype(np.float32) * fold)) / np.float64(fold)
-                else:
-                    Qr = w(f32_to_bf16_bits(Qr.astype(np.float32)))
+                # the matrix-core kernels fold softmax scale * log2(e) into the rotated query before rounding it; dividing
+                # the rounded value by the same factor gives the oracle exactly the scores the kernels form
+                fold = np.float32(1.0 / np.sqrt(case.head_dim)) * np.float32(1.4426950408889634)
+                Qr = w(f32_to_bf16_bits(Qr.astype(np.float32) * fold)) / np.float64(fold)
                 want = oracle.attention_positions(Kr, V, Qr, np.zeros(K.shape[0]), np.zeros(ln), n)
             else:   # the scalar kernel keeps the rotated values in fp32
                 want = case.oracle_out(0, c)
