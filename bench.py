@@ -69,6 +69,7 @@ def parse():
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
     ap.add_argument("--load-mode", type=int, default=0, help="library load_mode (0 staged copies for a host tier, 2 kernels read the tier in place)")
     ap.add_argument("--save-mode", type=int, default=0)
+    ap.add_argument("--two-call-save", action="store_true", help="append and save the new turn with the two separate calls in every leg")
     ap.add_argument("--depth", type=int, default=4, help="staging slots of the read stream (pipeline_depth) in the headline leg")
     ap.add_argument("--timeline-file", type=str, default="", help="write the per-interval timeline of the instrumented step here")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging only; marks the result invalid)")
@@ -383,6 +384,10 @@ def pipeline_figures(job, dt, steps, prof):
     """Section 3.2.1's quantities from the events of the timed steps of a host-tier run"""
     t_pipe = dt / steps
     cin_ms, cin_n = prof["copy_in"]; cout_ms, cout_n = prof["copy_out"]; att_ms, att_n = prof["attn"]
+    wb_kind = "copies out of a staging slot"
+    if cout_n == 0 and prof.get("pack", (0.0, 0))[1]:
+        cout_ms, cout_n = prof["pack"]          # the pack kernel writes the pinned tier in place: its run time is the write-back
+        wb_kind = "pack kernel storing to the pinned tier in place"
     t_in, t_out, t_attn = cin_ms / steps / 1e3, cout_ms / steps / 1e3, att_ms / steps / 1e3
     L = job.L
     # per token and layer, as the paper defines them: T_load = access time of one token's K/V, T_pref = prefill
@@ -395,7 +400,7 @@ def pipeline_figures(job, dt, steps, prof):
     return dict(
         ms_per_step=t_pipe * 1e3, tokens_per_s=job.tot_q / t_pipe, context_tokens_per_s=job.tot_k / t_pipe,
         h2d_gbs=link_gbs, d2h_gbs=job.link_out_bytes * cout_n / (cout_ms * 1e-3) / 1e9 if cout_ms else None,
-        copy_in_ms=t_in * 1e3, copy_out_ms=t_out * 1e3, attn_ms=t_attn * 1e3,
+        copy_in_ms=t_in * 1e3, copy_out_ms=cout_ms / steps, write_back=wb_kind, attn_ms=t_attn * 1e3,
         # (T_copy + T_attn - T_pipe) / min(T_copy, T_attn): 1.0 = the shorter one is completely hidden
         overlap_efficiency=(t_in + t_attn - t_pipe) / min(t_in, t_attn) if min(t_in, t_attn) > 0 else None,
         not_under_copy_ms=(t_pipe - t_in) * 1e3,
@@ -405,6 +410,20 @@ def pipeline_figures(job, dt, steps, prof):
             note="Section 3.2.1 with attention as the only compute: loading a layer takes longer than computing it, so the "
                  "pipeline is bound by the host link and the formula asks for a read buffer of nearly the whole stack"),
     )
+
+
+def mfma_rate_probe():
+    """the matrix-core rate the card sustains on zero and on random operands (a stand-alone program built with the
+    library, run as a child process); None when it is not built"""
+    exe = os.path.join(ROOT, "paper_2403_19708_amd", "mfma_rate_probe")
+    if not os.path.exists(exe):
+        return None
+    try:
+        import subprocess
+        out = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+        return json.loads(out.stdout.strip().splitlines()[-1]) if out.returncode == 0 else None
+    except Exception:
+        return None
 
 
 def link_probe(torch):
@@ -458,7 +477,7 @@ def timeline_figures(tl, path=None):
     length = lambda u: sum(b - a for a, b in u)
     cin, att = _union(by.get("copy_in", [])), _union(by.get("attn", []))
     comp = _union(by.get("attn", []) + by.get("unpack", []) + by.get("append", []))
-    cout = _union(by.get("copy_out", []))
+    cout = _union(by.get("copy_out", []) or by.get("pack", []))
     t0, t1 = min(a for _, a, _ in tl), max(b for _, _, b in tl)
     res = dict(span_ms=t1 - t0, copy_in_busy_ms=length(cin), attn_busy_ms=length(att), compute_busy_ms=length(comp),
                copy_out_busy_ms=length(cout), attn_under_copy_in_ms=_common(att, cin), copy_in_under_compute_ms=_common(cin, comp),
@@ -715,6 +734,8 @@ def main():
     stream = torch.cuda.current_stream()
 
     job = Job(torch, ca, args.config, args.seed, layers=args.layers)
+    if args.two_call_save:
+        job.fused_save = False
     cfg = job.cfg
     L = job.L
     log(f"[bench] {cfg['name']}: L={L} B={job.B} Hq={job.Hq} Hkv={job.Hkv} D={job.D} kept-history={job.tot_n} new={job.tot_q} tokens, "
@@ -745,7 +766,7 @@ def main():
     # the events around the attention call and the copies cost nothing measurable next to a link-bound step
     if args.tier == "pinned":
         src_k, src_v, tier_name = host_k, host_v, "pinned-host"
-        kinds = ["attn", "copy_in", "copy_out"]
+        kinds = ["attn", "copy_in", "copy_out", "pack"]
     else:
         src_k, src_v, tier_name = dev_k, dev_v, "HBM-resident"
         kinds = ["attn"]
@@ -793,6 +814,15 @@ def main():
     roof["algorithmic_bytes_per_launch"] = job.attn_bytes
     roof["launch"] = ("one ca_cached_prefill_attn call inside the timed steps: rotate_keys_kernel + attn_dma_kernel (+ combine_kernel "
                       "when keys are split)" if prerot else "one ca_cached_prefill_attn call inside the timed steps")
+    sustained = mfma_rate_probe()
+    if sustained:
+        log(f"[bench] matrix cores alone: {sustained['zero_operands_tflops']:.0f} TFLOP/s on zero operands, "
+            f"{sustained['random_operands_tflops']:.0f} TFLOP/s on random operands")
+    if sustained and job.attn_bound == "mfma":
+        # context for frac: what back-to-back matrix instructions alone reach on this card (clock under load)
+        roof["mfma_sustained"] = dict(sustained, frac_of_random_operand_rate=attn_live["tflops"] / sustained["random_operands_tflops"],
+                                      note="measured by paper_2403_19708_amd/mfma_rate_probe in this run: v_mfma_f32_32x32x16_bf16 "
+                                           "back to back, nothing else; peak above stays the published figure")
     traffic_file = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{args.config}.txt")
     if os.path.exists(traffic_file):
         kv = {}
@@ -914,6 +944,7 @@ def main():
         "hbm_resident_tier": hbm,
         "isolated": iso,
         "device_copy_gbs": copy_gbs,
+        "mfma_sustained": sustained,
         "pipeline_depth_sweep": sweep,
         "preload_sweep": preload,
         "configs": configs,

@@ -17,6 +17,8 @@ ROOT = os.path.dirname(HERE)
 SOURCES = ["ca_lib.hip", "ca_move.hip", "ca_attn_ref.hip", "ca_attn_dma.hip", "ca_attn_pp.hip", "ca_attn_decode.hip",
            "ca_store.cpp"]   # the last one is host code only (placement manager)
 LIB = os.path.join(HERE, "libca_hip.so")
+PROBE_SRC = os.path.join(HERE, "csrc", "mfma_rate_probe.hip")   # stand-alone measurement aid the benchmark runs
+PROBE = os.path.join(HERE, "mfma_rate_probe")
 
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
@@ -57,6 +59,14 @@ def build(verbose: bool = True) -> str:
             print(line)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed")
+    cmd = [hipcc(), "-O3", "--offload-arch=gfx950", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           PROBE_SRC, "-o", PROBE]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        print(proc.stderr)
+        raise RuntimeError("hipcc failed (mfma_rate_probe)")
     return LIB
 
 

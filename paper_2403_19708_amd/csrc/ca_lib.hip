@@ -1144,7 +1144,11 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
         total += r[i].e - r[i].b;
     }
     if (total > c.max_batch_kv_tokens) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_kv_save_layer: %lld tokens exceed a staging slot", (long long)total);
-    const bool staged = c.save_mode == 1 || (c.save_mode == 0 && any_host);
+    // Pinned destinations are written in place by the pack kernel unless staging is asked for: one kernel storing over
+    // the host link moves a turn four to five times faster than the per-conversation copies out of a staging slot
+    // (a few hundred KB each), which would bound the step as soon as a turn is longer than about a seventh of its history.
+    (void)any_host;
+    const bool staged = c.save_mode == 1;
 
     // saving starts after the producer of this layer's K/V: the work queued on `after_stream`, and the load of
     // this layer if one was issued (its unpack runs on an internal stream and may still be writing the pages a
@@ -1201,9 +1205,10 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
 }
 
 // Appending and saving the new turn in one call: the saved bytes ARE the appended bytes (keys without positions,
-// Section 3.4), so the pool need not be read back.  Device-accessible destinations: one kernel reads new_k/new_v once
-// and stores every vector twice (pool and tier).  Pinned destinations with staged saving: the copy-out on the save
-// stream reads new_k/new_v directly; no pack kernel, no staging slot.
+// Section 3.4), so the pool need not be read back.  Device destinations (and pinned ones under save_mode 2): one kernel
+// reads new_k/new_v once and stores every vector twice (pool and tier).  Pinned destinations by default: append kernel,
+// then the pack kernel writes the tier in place from the save stream.  Pinned destinations with staged saving: the
+// copy-out on the save stream reads new_k/new_v directly; no pack kernel, no staging slot.
 ca_status ca_kv_append_save_layer(ca_ctx *ctx, int32_t layer, const void *new_k, const void *new_v, void *k_pool,
                                   void *v_pool, void *const *dst_k, void *const *dst_v, void *stream_) {
     if (!ctx) return CA_ERR_INVALID_ARG;
@@ -1230,8 +1235,33 @@ ca_status ca_kv_append_save_layer(ca_ctx *ctx, int32_t layer, const void *new_k,
         if ((kk == MemKind::kDevice && !device_range_ok(dst_k[i], need)) || (kv == MemKind::kDevice && !device_range_ok(dst_v[i], need)))
             return fail(ctx, CA_ERR_INVALID_ARG, "ca_kv_append_save_layer: destination of conversation %d is smaller than hist_len + new_len tokens", i);
     }
-    const bool staged = c.save_mode == 1 || (c.save_mode == 0 && any_host);
+    const bool staged = c.save_mode == 1;
     hipStream_t stream = (hipStream_t)stream_;
+    if (!staged && any_host && c.save_mode == 0) {
+        // a pinned tier: the append kernel on the caller's stream, then the pack kernel on the save stream writes the
+        // new tokens to the tier in place (the caller's stream must not wait for stores that cross the host link)
+        std::vector<Segment> segs;
+        for (int i = 0; i < B; ++i)
+            segs.push_back({(uint8_t *)new_k, (uint8_t *)new_v, ctx->cu_q[i], ctx->n_keep[i], ctx->new_len[i], i});
+        int iv;
+        CA_HIP(ctx, prof_begin(ctx, kProfAppend, stream, &iv));
+        st = run_move(ctx, true, segs, k_pool, v_pool, stream);
+        if (st != CA_OK) return st;
+        CA_HIP(ctx, prof_end(ctx, iv, stream));
+        CA_HIP(ctx, hipEventRecord(ctx->ev_after, stream));
+        CA_HIP(ctx, hipStreamWaitEvent(ctx->s_save, ctx->ev_after, 0));
+        if (ctx->loaded[layer]) CA_HIP(ctx, hipStreamWaitEvent(ctx->s_save, ctx->ev_ready[layer], 0));
+        segs.clear();
+        for (int i = 0; i < B; ++i)
+            if (ctx->new_len[i] > 0)
+                segs.push_back({(uint8_t *)dst_k[i], (uint8_t *)dst_v[i], ctx->hist_len[i], ctx->n_keep[i], ctx->new_len[i], i});
+        int iv_pack;
+        CA_HIP(ctx, prof_begin(ctx, kProfPack, ctx->s_save, &iv_pack));
+        st = run_move(ctx, false, segs, k_pool, v_pool, ctx->s_save);
+        if (st != CA_OK) return st;
+        CA_HIP(ctx, prof_end(ctx, iv_pack, ctx->s_save));
+        return CA_OK;
+    }
     if (staged) {
         // append on the caller's stream; the copy-out follows it on the save stream, straight from new_k / new_v
         std::vector<Segment> segs;

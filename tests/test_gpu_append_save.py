@@ -10,7 +10,7 @@ from harness import Case, GpuRun, torch_to_bits
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("tier,save_mode", [("device", 0), ("pinned", 0), ("pinned", 2), ("device", 1)])
+@pytest.mark.parametrize("tier,save_mode", [("device", 0), ("pinned", 0), ("pinned", 1), ("pinned", 2), ("device", 1)])
 def test_append_save_bit_exact(tier, save_mode):
     # non-page-aligned kept histories, a conversation without history, one whose new turn is a single token
     case = Case([333, 0, 90, 515], [17, 129, 1, 64], [77, 0, 90, 3], 8, 2, 128, seed=41)

@@ -105,7 +105,7 @@ def test_rebase_metadata_bit_exact(case):
         run.close()
 
 
-@pytest.mark.parametrize("tier,mode", [("pinned", 0), ("pinned", 2), ("device", 0), ("device", 1)])
+@pytest.mark.parametrize("tier,mode", [("pinned", 0), ("pinned", 1), ("pinned", 2), ("device", 0), ("device", 1)])
 def test_load_append_save_bit_exact(case, tier, mode):
     run = GpuRun(case, tier=tier, load_mode=mode, save_mode=mode)
     try:

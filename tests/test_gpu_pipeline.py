@@ -50,12 +50,13 @@ def test_pipeline_orderings_give_identical_bits():
     overlapped one: staging slots are reused every `depth` layers, pools start as NaN patterns."""
     case = Case([300, 64, 0, 777], [40, 130, 9, 257], [20, 0, 0, 300], 4, 2, 128, seed=51, n_layers=6, window=1024)
     ref_out, ref_tier = run_stack(case, "pinned", depth=1, mode=1, sync_every_op=True)
-    for tier, depth, mode in (("pinned", 1, 0), ("pinned", 2, 0), ("pinned", 3, 0), ("pinned", 2, 2), ("device", 2, 0), ("device", 2, 1)):
-        out, saved = run_stack(case, tier, depth, mode)
+    for tier, depth, mode, save_mode in (("pinned", 1, 0, 0), ("pinned", 2, 0, 0), ("pinned", 3, 0, 1), ("pinned", 2, 2, 2), ("pinned", 2, 0, 1),
+                                         ("device", 2, 0, 0), ("device", 2, 1, 1)):
+        out, saved = run_stack(case, tier, depth, mode, save_mode=save_mode)
         for l in range(case.n_layers):
-            assert np.array_equal(out[l], ref_out[l]), (tier, depth, mode, l)
+            assert np.array_equal(out[l], ref_out[l]), (tier, depth, mode, save_mode, l)
             for a, b in zip(saved[l], ref_tier[l]):
-                assert np.array_equal(a, b), (tier, depth, mode, l)
+                assert np.array_equal(a, b), (tier, depth, mode, save_mode, l)
     # and the reference itself is right: every layer against the oracle
     for l in range(case.n_layers):
         at = 0
@@ -261,7 +262,7 @@ def test_config2_full_size_stack_on_the_pinned_tier_every_output():
 
 def test_event_timeline_respects_the_order_the_streams_must_keep():
     """The library's own event pairs, read on one clock: per layer the attention starts after that layer's
-    unpack has ended, the unpack after its copy-in, the write-back after the attention; reading the timeline
+    unpack has ended, the unpack after its copy-in, the write-back kernel after the attention; reading the timeline
     does not consume the intervals."""
     case = Case([300, 64, 0, 777], [40, 130, 9, 257], [20, 0, 0, 300], 4, 2, 128, seed=52, n_layers=5, window=1024)
     run = GpuRun(case, tier="pinned", pipeline_depth=2, load_mode=0)
@@ -285,7 +286,7 @@ def test_event_timeline_respects_the_order_the_streams_must_keep():
             assert b >= a >= 0.0
             per.setdefault(kind, []).append((a, b))
         L = case.n_layers
-        for kind in ("copy_in", "attn", "copy_out"):
+        for kind in ("copy_in", "attn", "pack"):
             assert len(per[kind]) == L, (kind, len(per[kind]))
         for kind in per:
             ms, n = run.ctx.profile_read(kind)
@@ -299,6 +300,6 @@ def test_event_timeline_respects_the_order_the_streams_must_keep():
             unpack_begin = min(a for a, _ in per["unpack"][l * n_unpack:(l + 1) * n_unpack])
             assert unpack_begin >= per["copy_in"][l][1] - eps, l
             assert per["attn"][l][0] >= unpack_end - eps, l
-            assert per["copy_out"][l][0] >= per["attn"][l][1] - eps, l
+            assert per["pack"][l][0] >= per["attn"][l][1] - eps, l      # the write-back kernel of the layer (pinned tier, in place)
     finally:
         run.close()
