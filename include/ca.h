@@ -78,12 +78,17 @@ typedef struct {
     int32_t load_mode;       /* 0: choose per source pointer; 1: copy into a staging slot,    */
                              /* then unpack; 2: the unpack kernel reads the source in place   */
                              /* (source must be device-accessible)                            */
-    int32_t save_mode;       /* for ca_kv_save_layer / ca_kv_append_save_layer: 0 the pack kernel */
-                             /* writes the destination in place, pinned host included, from the   */
-                             /* internal save stream; 1 pack into a staging slot, then one copy   */
-                             /* per conversation (several times slower over the host link: a copy */
-                             /* is a few hundred KB); 2 as 0, and ca_kv_append_save_layer stores  */
-                             /* to a pinned tier from the kernel on the caller's stream           */
+    int32_t save_mode;       /* for ca_kv_save_layer / ca_kv_append_save_layer.  Device memory is  */
+                             /* written in place by the pack kernel unless 1.  Pinned host memory: */
+                             /* 1 pack into a staging slot, then one copy per conversation on a    */
+                             /* copy engine (about 8 GB/s for turns of a few hundred tokens, and   */
+                             /* disturbs no kernel); 2 the pack kernel stores over the host link   */
+                             /* from the internal save stream (about 40 GB/s, but kernels running  */
+                             /* beside it are held up for about as long as it runs; with 2         */
+                             /* ca_kv_append_save_layer stores from the one kernel on the caller's */
+                             /* stream); 0 chooses per call: staged while the tokens to save are   */
+                             /* fewer than a fifth of the kept history loaded per layer (the       */
+                             /* copies then hide under the load), else in place                    */
     int32_t attn_variant;    /* 0: choose (the streaming kernel for a batch of decode steps, else the    */
                              /* matrix-core kernel); 1: scalar fp32 kernel (slow, for checking); 2: the  */
                              /* matrix-core kernel, K/V loaded straight into LDS, whatever the batch;    */
@@ -240,8 +245,9 @@ ca_status ca_cached_prefill_attn_static(ca_ctx *ctx, int32_t layer, const void *
  * (contiguous layout, pointer to saved token 0) starting at token dst_tok_offset[c] (host int64
  * array; NULL means hist_len[c], i.e. append behind the saved history).  Keys leave without
  * positional encoding, exactly as stored.  Runs on the internal save stream after the work
- * queued so far on `after_stream`.  Destinations: device memory or pinned host memory, written in
- * place by the pack kernel (save_mode 1: pack kernel into a ring slot + hipMemcpyAsync).          */
+ * queued so far on `after_stream`.  Destinations: device memory (written in place by the pack
+ * kernel) or pinned host memory (pack kernel into a ring slot + hipMemcpyAsync, or written in place:
+ * see save_mode).                                                                                  */
 ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
                            const int32_t *tok_end, const void *k_pool, const void *v_pool,
                            void *const *dst_k, void *const *dst_v, const int64_t *dst_tok_offset,
@@ -251,12 +257,11 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
  * saved history of every conversation) in one call that reads new_k / new_v once: what is saved IS
  * what is appended, keys without positional encoding (Sections 3.2.2, 3.4), so the pool is not read
  * back.  Device destinations (and pinned ones under save_mode 2): one kernel on `stream` stores every
- * vector twice, to its page and to its row of the tier.  Pinned destinations by default: the append
- * kernel runs on `stream` and the pack kernel follows on the internal save stream, writing the tier in
- * place.  Pinned destinations under save_mode 1: the append kernel runs on `stream` and one copy per
- * conversation follows on the save stream straight from new_k / new_v (no pack kernel, no staging
- * slot); new_k / new_v must then stay unchanged until ca_sync or ca_join.  Same arguments, checks and
- * statuses as the two calls it replaces.                                                            */
+ * vector twice, to its page and to its row of the tier.  Pinned destinations otherwise: the append
+ * kernel runs on `stream`; then either one copy per conversation follows on the internal save stream
+ * straight from new_k / new_v (no pack kernel, no staging slot; new_k / new_v must then stay unchanged
+ * until ca_sync or ca_join), or the pack kernel follows there and writes the tier in place (see
+ * save_mode for which).  Same arguments, checks and statuses as the two calls it replaces.          */
 ca_status ca_kv_append_save_layer(ca_ctx *ctx, int32_t layer, const void *new_k, const void *new_v,
                                   void *k_pool, void *v_pool, void *const *dst_k, void *const *dst_v,
                                   void *stream);

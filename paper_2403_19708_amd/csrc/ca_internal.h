@@ -42,6 +42,8 @@ struct MoveShape {
     int32_t heads_per_wg;        // heads one workgroup moves (grid.x slices the heads, and K/V)
     int32_t n_in_launch;
     int32_t max_pages_touched;   // largest number of pages a range of this launch touches
+    int32_t max_grid_y;          // 0: one workgroup row per page; > 0: at most this many rows, each walking several pages
+                                 // (a kernel that stores over the host link is bound by the link and should hold few compute units)
 };
 
 // to_pool = true: contiguous -> pages (unpack / append); false: pages -> contiguous (pack).

@@ -109,6 +109,20 @@ ca_status fail(ca_ctx *ctx, ca_status st, const char *fmt, ...) {
         }                                                                                        \
     } while (0)
 
+constexpr int kHostStoreWorkgroups = 128;   // workgroups of a pack kernel whose destination is pinned host memory
+
+// How a save reaches a pinned tier when the configuration leaves the choice to the library (save_mode 0).  Measured on
+// MI355X with 64 conversations per layer: the per-conversation copies out of a staging slot (a few hundred KB each)
+// move about 8 GB/s, run on a copy engine and disturb nothing; a pack kernel that stores over the host link moves about
+// 40 GB/s, but while it runs an attention kernel beside it takes about that much longer (the slow stores hold up the
+// queues its own stores go through).  The copies are the better choice as long as they hide under the layer's load
+// (about 50 GB/s): fewer than a fifth as many tokens to save as kept history to load.  Beyond that the save stream
+// would bound the step, and the kernel's bounded cost is the smaller one.
+bool host_save_in_place(const ca_ctx *ctx, int64_t tokens_to_save) {
+    if (ctx->cfg.save_mode != 0) return ctx->cfg.save_mode == 2;
+    return tokens_to_save * 5 > ctx->total_n;
+}
+
 enum ProfileKind { kProfCopyIn = 0, kProfUnpack = 1, kProfAppend = 2, kProfAttn = 3, kProfPack = 4, kProfCopyOut = 5, kProfKinds = 6 };
 
 hipError_t prof_event(ca_ctx *ctx, hipEvent_t *ev) {
@@ -933,8 +947,9 @@ struct Segment {  // one conversation's share of a move
     int32_t ctx_tok0, count, seq;
 };
 
+// narrow_workgroups > 0: launch about that many workgroups at most (each then walks several pages)
 ca_status run_move(ca_ctx *ctx, bool to_pool, const std::vector<Segment> &segs, void *k_pool, void *v_pool,
-                   hipStream_t stream) {
+                   hipStream_t stream, int narrow_workgroups = 0) {
     const ca_config &c = ctx->cfg;
     MoveShape shape{};
     shape.block_table = (const int32_t *)(ctx->d_meta + ctx->off_table);
@@ -961,6 +976,10 @@ ca_status run_move(ca_ctx *ctx, bool to_pool, const std::vector<Segment> &segs, 
         }
         shape.n_in_launch = n;
         shape.max_pages_touched = max_touched;
+        if (narrow_workgroups > 0) {
+            const int slices = (c.n_kv_heads + shape.heads_per_wg - 1) / shape.heads_per_wg;
+            shape.max_grid_y = std::max(1, narrow_workgroups / (2 * slices * n));
+        }
         CA_HIP(ctx, launch_move(to_pool, args, shape, (uint8_t *)k_pool, (uint8_t *)v_pool, stream));
     }
     return CA_OK;
@@ -1144,11 +1163,7 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
         total += r[i].e - r[i].b;
     }
     if (total > c.max_batch_kv_tokens) return fail(ctx, CA_ERR_OUT_OF_RANGE, "ca_kv_save_layer: %lld tokens exceed a staging slot", (long long)total);
-    // Pinned destinations are written in place by the pack kernel unless staging is asked for: one kernel storing over
-    // the host link moves a turn four to five times faster than the per-conversation copies out of a staging slot
-    // (a few hundred KB each), which would bound the step as soon as a turn is longer than about a seventh of its history.
-    (void)any_host;
-    const bool staged = c.save_mode == 1;
+    const bool staged = any_host ? !host_save_in_place(ctx, total) : c.save_mode == 1;
 
     // saving starts after the producer of this layer's K/V: the work queued on `after_stream`, and the load of
     // this layer if one was issued (its unpack runs on an internal stream and may still be writing the pages a
@@ -1197,7 +1212,9 @@ ca_status ca_kv_save_layer(ca_ctx *ctx, int32_t layer, const int32_t *tok_begin,
         }
         int iv_pack;
         CA_HIP(ctx, prof_begin(ctx, kProfPack, ctx->s_save, &iv_pack));
-        st = run_move(ctx, false, segs, (void *)k_pool, (void *)v_pool, ctx->s_save);
+        // stores that cross the host link are bound by the link: a few workgroups saturate it, and a grid that filled the
+        // GPU with waiting wavefronts would take the compute units from the attention kernel running beside it
+        st = run_move(ctx, false, segs, (void *)k_pool, (void *)v_pool, ctx->s_save, any_host ? kHostStoreWorkgroups : 0);
         if (st != CA_OK) return st;
         CA_HIP(ctx, prof_end(ctx, iv_pack, ctx->s_save));
     }
@@ -1235,7 +1252,7 @@ ca_status ca_kv_append_save_layer(ca_ctx *ctx, int32_t layer, const void *new_k,
         if ((kk == MemKind::kDevice && !device_range_ok(dst_k[i], need)) || (kv == MemKind::kDevice && !device_range_ok(dst_v[i], need)))
             return fail(ctx, CA_ERR_INVALID_ARG, "ca_kv_append_save_layer: destination of conversation %d is smaller than hist_len + new_len tokens", i);
     }
-    const bool staged = c.save_mode == 1;
+    const bool staged = any_host ? !host_save_in_place(ctx, ctx->total_q) : c.save_mode == 1;
     hipStream_t stream = (hipStream_t)stream_;
     if (!staged && any_host && c.save_mode == 0) {
         // a pinned tier: the append kernel on the caller's stream, then the pack kernel on the save stream writes the
@@ -1257,7 +1274,7 @@ ca_status ca_kv_append_save_layer(ca_ctx *ctx, int32_t layer, const void *new_k,
                 segs.push_back({(uint8_t *)dst_k[i], (uint8_t *)dst_v[i], ctx->hist_len[i], ctx->n_keep[i], ctx->new_len[i], i});
         int iv_pack;
         CA_HIP(ctx, prof_begin(ctx, kProfPack, ctx->s_save, &iv_pack));
-        st = run_move(ctx, false, segs, k_pool, v_pool, ctx->s_save);
+        st = run_move(ctx, false, segs, k_pool, v_pool, ctx->s_save, kHostStoreWorkgroups);
         if (st != CA_OK) return st;
         CA_HIP(ctx, prof_end(ctx, iv_pack, ctx->s_save));
         return CA_OK;

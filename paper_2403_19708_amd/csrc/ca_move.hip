@@ -133,7 +133,9 @@ hipError_t launch_move(bool to_pool, const MoveArgs &args, const MoveShape &shap
                        uint8_t *v_pool, hipStream_t stream) {
     if (shape.n_in_launch <= 0 || shape.max_pages_touched <= 0) return hipSuccess;
     const int slices = (shape.n_kv_heads + shape.heads_per_wg - 1) / shape.heads_per_wg;
-    dim3 grid(2 * slices, std::min(shape.max_pages_touched, kMoveMaxGridY), shape.n_in_launch);
+    int rows = std::min(shape.max_pages_touched, kMoveMaxGridY);
+    if (shape.max_grid_y > 0) rows = std::min(rows, shape.max_grid_y);
+    dim3 grid(2 * slices, rows, shape.n_in_launch);
     // nontemporal accesses: every byte is touched once (measured ~5 % faster than cached ones)
     if (to_pool)
         hipLaunchKernelGGL((move_kernel<true, true>), grid, dim3(kMoveThreads), 0, stream, args, shape, k_pool, v_pool);

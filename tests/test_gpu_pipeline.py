@@ -265,7 +265,7 @@ def test_event_timeline_respects_the_order_the_streams_must_keep():
     unpack has ended, the unpack after its copy-in, the write-back kernel after the attention; reading the timeline
     does not consume the intervals."""
     case = Case([300, 64, 0, 777], [40, 130, 9, 257], [20, 0, 0, 300], 4, 2, 128, seed=52, n_layers=5, window=1024)
-    run = GpuRun(case, tier="pinned", pipeline_depth=2, load_mode=0)
+    run = GpuRun(case, tier="pinned", pipeline_depth=2, load_mode=0, save_mode=2)     # write-back by the pack kernel, in place
     try:
         stream = torch.cuda.Stream()
         run.ctx.profile_enable(True)
