@@ -186,9 +186,9 @@ int cao_cached_attention(const double *Kh, const double *Vh, int Lh,
  * policy 0: keep the most recent floor(W*(1-ratio)) tokens of the context
  *           (history + new); the new turn is never dropped.
  * policy 1: drop floor(W*ratio) oldest tokens, again while the context still overflows
- *           ("cut off the first 2K tokens" for a 4K window).
+ *           (the passage that drops the oldest 2K tokens of a 4K window).
  * policy 2: drop the earliest floor(ratio * context) tokens, again while it still
- *           overflows ("discard the earliest half of the tokens").
+ *           overflows (the passage that reads ratio 0.5 as dropping the older half of the tokens).
  * keep_start_out[c] = index of the first surviving history token (<= hist).
  */
 int cao_truncate_plan(const int32_t *hist_len, const int32_t *new_len, int32_t W, double ratio,
