@@ -253,9 +253,14 @@ class Job:
     def step(self, ctx, src_k, src_v, stream):
         """the whole path for one batch: the read stream runs ahead as far as its staging slots allow"""
         self.rebase(ctx, stream)
-        for l in range(self.L):
+        # loads are queued a few layers ahead of the compute calls (queueing all of them first would keep the host
+        # busy for several milliseconds before the first attention is queued: a load is 2 copies per conversation)
+        ahead = min(self.L, 6)
+        for l in range(ahead):
             ctx.kv_load_layer(l, src_k[l], src_v[l], self.k_pool[l], self.v_pool[l])
         for l in range(self.L):
+            if l + ahead < self.L:
+                ctx.kv_load_layer(l + ahead, src_k[l + ahead], src_v[l + ahead], self.k_pool[l + ahead], self.v_pool[l + ahead])
             self.compute_layer(ctx, l, src_k, src_v, stream)
         ctx.join(stream)
 

@@ -170,7 +170,8 @@ ca_status ca_truncate_plan(const int32_t *hist_len, const int32_t *new_len, int3
                            double ratio, int32_t policy, int32_t n, int32_t *keep_start_out);
 
 /* The same overflow rule as policy 0, with a discarding list that spares the first n_sink saved
- * tokens (Section 3.4: "selective preservation", e.g. the initial tokens): without overflow
+ * tokens (Section 3.4, last paragraph: keeping chosen tokens, for instance the first ones of a
+ * text, instead of a plain suffix): without overflow
  * conversation c keeps one range [0, hist_len); on overflow it keeps floor(window*(1-ratio)) -
  * new_len history tokens (0 if negative): the first min(n_sink, that many) and the most recent
  * rest.  ranges_out: [n][2][2] (two (begin, end) slots per conversation, unused ones 0, 0);
