@@ -69,6 +69,7 @@ def parse():
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
     ap.add_argument("--load-mode", type=int, default=0, help="library load_mode (0 staged copies for a host tier, 2 kernels read the tier in place)")
     ap.add_argument("--save-mode", type=int, default=0)
+    ap.add_argument("--loads-ahead", type=int, default=0, help="layers whose loads are queued ahead of the compute calls (0: all first)")
     ap.add_argument("--two-call-save", action="store_true", help="append and save the new turn with the two separate calls in every leg")
     ap.add_argument("--depth", type=int, default=4, help="staging slots of the read stream (pipeline_depth) in the headline leg")
     ap.add_argument("--timeline-file", type=str, default="", help="write the per-interval timeline of the instrumented step here")
@@ -238,6 +239,7 @@ class Job:
     def rebase(self, ctx, stream):
         ctx.rope_rebase(self.hist, self.keep_start, self.new, self.block_table, self.num_pages, stream)
 
+    loads_ahead = 0        # layers whose loads are queued before the first compute call (0: all of them)
     fused_save = True      # the new turn is appended and saved by one call that reads it once (False: the two calls)
 
     def compute_layer(self, ctx, l, src_k, src_v, stream, save=True):
@@ -253,9 +255,11 @@ class Job:
     def step(self, ctx, src_k, src_v, stream):
         """the whole path for one batch: the read stream runs ahead as far as its staging slots allow"""
         self.rebase(ctx, stream)
-        # loads are queued a few layers ahead of the compute calls (queueing all of them first would keep the host
-        # busy for several milliseconds before the first attention is queued: a load is 2 copies per conversation)
-        ahead = min(self.L, 6)
+        # All loads are queued first.  That keeps the host busy for about 6 ms before the first attention is queued (a
+        # load is 2 copies per conversation), but queueing them a few layers ahead of the compute calls instead was
+        # measured to lower the link rate of the whole step (config 5: 1030-1036 ms per step against 1073-1119 ms with
+        # 6 or 12 layers ahead): the copy queues run dry whenever the host is busy with the other calls.
+        ahead = min(self.L, self.loads_ahead) if self.loads_ahead > 0 else self.L
         for l in range(ahead):
             ctx.kv_load_layer(l, src_k[l], src_v[l], self.k_pool[l], self.v_pool[l])
         for l in range(self.L):
@@ -741,6 +745,7 @@ def main():
     job = Job(torch, ca, args.config, args.seed, layers=args.layers)
     if args.two_call_save:
         job.fused_save = False
+    job.loads_ahead = args.loads_ahead
     cfg = job.cfg
     L = job.L
     log(f"[bench] {cfg['name']}: L={L} B={job.B} Hq={job.Hq} Hkv={job.Hkv} D={job.D} kept-history={job.tot_n} new={job.tot_q} tokens, "
