@@ -211,23 +211,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void attn_dma_kernel(AttnArgs a) {
     // The softmax scale and log2(e) are folded into the rotated query before it is rounded to bf16, so the scores
     // come out of the matrix cores in the units of the base-2 exponent.
     const float cscale = a.softmax_scale * 1.4426950408889634f;
-    bf16x8 Qf[KSTEPS];
-    {
-        const uint16_t *qrow = a.q + ((int64_t)(q0 + j) * a.n_q_heads + head) * D;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS / 2; ++ks) {
-            const int piece = 2 * ks + half;
-            uint4 x = *reinterpret_cast<const uint4 *>(qrow + 8 * piece);
-            uint4 y = *reinterpret_cast<const uint4 *>(qrow + HALF + 8 * piece);
-            float2 cs[8];
-            load_cs<D, STYLE>(a.rope, qpos, piece, cs);
-            uint32_t *px = reinterpret_cast<uint32_t *>(&x), *py = reinterpret_cast<uint32_t *>(&y);
-#pragma unroll
-            for (int w = 0; w < 4; ++w) rotate_dword<STYLE>(px[w], py[w], cs, w, cscale);
-            Qf[ks] = __builtin_bit_cast(bf16x8, x);
-            Qf[ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, y);
-        }
-    }
+    bf16x8 Qf[KSTEPS];          // loaded and rotated in the prologue, once the first key/value tiles are on their way
 
     // ---- rotary pass: this thread's (key, piece pair) of every K tile ------------------------------
     const bool rot_active = ROT && (ROT_TASKS >= NTHREADS || tid < ROT_TASKS);
@@ -360,6 +344,24 @@ __global__ __launch_bounds__(64 * NW, OCC) void attn_dma_kernel(AttnArgs a) {
     issue(t_begin);
     if (NS > 2 && t_begin + 1 < n_tiles) issue(t_begin + 1);
     if (NS > 3 && t_begin + 2 < n_tiles) issue(t_begin + 2);
+    // The query row is fetched behind the tile loads, so its latency and theirs overlap.  These loads are younger than
+    // the tile loads and complete after them: the counted wait below can only become stricter by them.
+    {
+        const uint16_t *qrow = a.q + ((int64_t)(q0 + j) * a.n_q_heads + head) * D;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS / 2; ++ks) {
+            const int piece = 2 * ks + half;
+            uint4 x = *reinterpret_cast<const uint4 *>(qrow + 8 * piece);
+            uint4 y = *reinterpret_cast<const uint4 *>(qrow + HALF + 8 * piece);
+            float2 cs[8];
+            load_cs<D, STYLE>(a.rope, qpos, piece, cs);
+            uint32_t *px = reinterpret_cast<uint32_t *>(&x), *py = reinterpret_cast<uint32_t *>(&y);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) rotate_dword<STYLE>(px[w], py[w], cs, w, cscale);
+            Qf[ks] = __builtin_bit_cast(bf16x8, x);
+            Qf[ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, y);
+        }
+    }
     if (NS > 3 && t_begin + 2 < n_tiles) { CA_WAIT_VMCNT(NI); } else { CA_WAIT_VMCNT(0); }   // the first two tiles have landed
     __syncthreads();
     rot_read(ring + (t_begin % NS) * STAGE);
