@@ -63,3 +63,28 @@ def test_append_save_equals_the_two_calls_on_a_d64_stack():
             assert np.array_equal(a, b)
     for a, b in zip(outs[0][2], outs[1][2]):
         assert np.array_equal(a, b)
+
+
+def test_default_save_mode_picks_the_write_back_by_the_plan():
+    """save_mode 0 on a pinned tier: copies out of a staging slot while the tokens to save are fewer than a fifth of
+    the kept history loaded per layer, the pack kernel storing in place beyond that; the saved bits are the same."""
+    few = Case([600, 500], [20, 30], [0, 0], 4, 2, 128, seed=43)          # 50 new against 1100 kept
+    many = Case([100, 90], [60, 70], [0, 0], 4, 2, 128, seed=44)          # 130 new against 190 kept
+    for case, staged in ((few, True), (many, False)):
+        run = GpuRun(case, tier="pinned")
+        try:
+            run.rebase()
+            run.load(0)
+            run.ctx.profile_enable(True)
+            run.ctx.kv_append_save_layer(0, run.k_new[0], run.v_new[0], run.k_pool[0], run.v_pool[0], run.host_k[0], run.host_v[0])
+            run.finish()
+            run.ctx.profile_enable(False)
+            n_copy_out, n_pack = run.ctx.profile_read("copy_out")[1], run.ctx.profile_read("pack")[1]
+            assert (n_copy_out, n_pack) == ((1, 0) if staged else (0, 1)), (staged, n_copy_out, n_pack)
+            for which, host in (("k", run.host_k[0]), ("v", run.host_v[0])):
+                for c in range(case.B):
+                    got = torch_to_bits(host[c])
+                    assert np.array_equal(got[:case.hist_len[c]], case.tensor(0, f"{which}_hist", c)), (which, c)
+                    assert np.array_equal(got[case.hist_len[c]:], case.tensor(0, f"{which}_new", c)), (which, c)
+        finally:
+            run.close()
