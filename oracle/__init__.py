@@ -9,6 +9,7 @@ from .ca_oracle import (  # noqa: F401
     build,
     cached_attention,
     cached_attention_kept,
+    compact_tier,
     kept_indices_sinks,
     kv_bytes_per_token,
     n_threads,

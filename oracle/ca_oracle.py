@@ -151,6 +151,14 @@ def cached_attention_kept(Kh, Vh, kept, Qn, Kn, Vn, **kw):
     return cached_attention(np.asarray(Kh)[kept], np.asarray(Vh)[kept], Qn, Kn, Vn, keep_start=0, **kw)
 
 
+def compact_tier(rows, ranges) -> np.ndarray:
+    """Section 3.4, last paragraph: the saved cache of a conversation after the discarded tokens have been
+    dropped from the store: the rows of the kept ranges [(begin, end), ...] (increasing, disjoint), in order."""
+    rows = np.asarray(rows)
+    out = [rows[int(b):int(e)] for b, e in ranges]
+    return np.concatenate(out) if out else rows[:0].copy()
+
+
 def kept_indices_sinks(hist_len, new_len, window: int, ratio: float = 0.5, n_sink: int = 4) -> list:
     """Discarding list that spares the first n_sink saved tokens: without overflow everything is kept; on
     overflow (hist + new > window) the history may keep floor(window*(1-ratio)) - new tokens (not below 0,

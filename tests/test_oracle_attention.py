@@ -232,6 +232,24 @@ def test_pruned_history_equals_recompute_over_the_kept_tokens(kept_kind):
         assert np.abs(got - other).max() > 1e-3
 
 
+def test_compacted_store_gives_what_the_discarding_list_gave():
+    """Dropping the discarded rows from the store and then reusing everything that is left is the reuse over the
+    pruned history (which is pinned to a full recompute above); hand-checked rows, the empty list and the identity."""
+    Lh, Ln, Hq, Hkv, D = 70, 9, 4, 2, 64
+    Q, K, V = make_case(Lh, Ln, Hq, Hkv, D, seed=8)
+    ranges = [(0, 3), (10, 11), (40, 70)]
+    kept = np.r_[0:3, 10:11, 40:70]
+    Kc, Vc = oracle.compact_tier(K[:Lh], ranges), oracle.compact_tier(V[:Lh], ranges)
+    assert Kc.shape[0] == 34 and np.array_equal(Kc[3], K[10]) and np.array_equal(Kc[4], K[40]) and np.array_equal(Vc[-1], V[69])
+    got = oracle.cached_attention(Kc, Vc, Q[Lh:], K[Lh:], V[Lh:], keep_start=0)
+    want = oracle.cached_attention_kept(K[:Lh], V[:Lh], kept, Q[Lh:], K[Lh:], V[Lh:])
+    assert np.array_equal(got, want)
+    assert oracle.compact_tier(K[:Lh], []).shape == (0,) + K.shape[1:]
+    assert np.array_equal(oracle.compact_tier(K[:Lh], [(0, Lh)]), K[:Lh])
+    # a planted mistake (one range taken one row too early) is seen
+    assert not np.array_equal(oracle.compact_tier(K[:Lh], [(0, 3), (9, 10), (40, 70)]), Kc)
+
+
 def test_sink_discarding_list_closed_forms():
     """Budget arithmetic of the sink-sparing list against hand-computed cases (window 4096, ratio 0.5:
     2048 tokens of [history | new] survive an overflow, as in Section 4.1's 4K/2K setting)."""
