@@ -181,6 +181,21 @@ ca_status ca_truncate_plan_sinks(const int32_t *hist_len, const int32_t *new_len
                                  double ratio, int32_t n_sink, int32_t n, int32_t *ranges_out,
                                  int32_t *count_out);
 
+/* Section 3.4, last paragraph: drops the discarded tokens from the saved cache itself.  For every
+ * conversation the rows of its kept tokens -- the ranges of keep_ranges / keep_range_count exactly
+ * as in ca_batch, or [keep_start[c], hist_len[c]) when keep_ranges is NULL -- are moved to the
+ * front of tier_k[c] and tier_v[c] in order, and hist_len_out[c] receives how many rows are left
+ * (pass it as hist_len, with keep_start 0, from then on).  One layer's buffers per call.
+ * tier_k / tier_v: HOST memory (pinned or not), [hist_len[c]] rows of row_bytes =
+ * n_kv_heads * head_dim * 2 bytes; the move is done by the calling thread with memmove, so no
+ * load or save of these buffers may be in flight (ca_sync first).  Arguments are checked before
+ * anything moves: CA_ERR_OUT_OF_RANGE for ranges that are empty, not increasing, overlapping or
+ * outside [0, hist_len].  Needs no context and no GPU.                                          */
+ca_status ca_tier_compact(int32_t n_seqs, const int32_t *hist_len, const int32_t *keep_start,
+                          const int32_t *keep_ranges, const int32_t *keep_range_count,
+                          int64_t row_bytes, void *const *tier_k, void *const *tier_v,
+                          int32_t *hist_len_out);
+
 /* ---- Section 3.4: position rebasing --------------------------------------------------- */
 /* Makes `batch` the context's current plan: numbers the kept tokens of every conversation
  * from 0 (keys 0..context-1, new token j at n_keep + j), and builds on the device the

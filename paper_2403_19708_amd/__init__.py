@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     load_library,
     pointer_array,
     truncate_plan,
+    tier_compact,
     truncate_plan_sinks,
 )

@@ -24,7 +24,7 @@ SYMBOLS = ["ca_config_default", "ca_config_validate", "ca_batch_validate", "ca_c
            "ca_last_error", "ca_status_string", "ca_truncate_plan", "ca_truncate_plan_sinks", "ca_rope_rebase", "ca_rebase_read",
            "ca_kv_load_layer", "ca_kv_append_layer", "ca_cached_prefill_attn", "ca_cached_prefill_attn_static",
            "ca_kv_save_layer", "ca_kv_append_save_layer",
-           "ca_sync", "ca_join", "ca_profile_enable", "ca_profile_read", "ca_profile_timeline"]
+           "ca_sync", "ca_join", "ca_profile_enable", "ca_profile_read", "ca_profile_timeline", "ca_tier_compact"]
 
 
 class CaError(RuntimeError):
@@ -112,6 +112,9 @@ def load_library():
     lib.ca_profile_read.restype = C.c_int
     lib.ca_profile_timeline.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int64, i64p]
     lib.ca_profile_timeline.restype = C.c_int
+    lib.ca_tier_compact.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                    C.c_int64, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_int32)]
+    lib.ca_tier_compact.restype = C.c_int
     _lib = lib
     return lib
 
@@ -243,6 +246,33 @@ def truncate_plan_sinks(hist_len, new_len, window: int, ratio: float = 0.5, n_si
     if st != 0:
         raise CaError(st, "ca_truncate_plan_sinks rejected its arguments")
     return [[(int(rng[c, r, 0]), int(rng[c, r, 1])) for r in range(int(cnt[c]))] for c in range(h.shape[0])]
+
+
+def tier_compact(hist_len, keep, row_bytes: int, tier_k, tier_v) -> np.ndarray:
+    """Drops the discarded rows of one layer's saved cache in host memory (ca_tier_compact).  keep: per conversation
+    either a keep_start (int) or a list of (begin, end) kept ranges; tier_k / tier_v: per conversation a host address
+    (int) or an object with data_ptr() (a CPU or pinned torch tensor).  Returns the new history lengths."""
+    lib = load_library()
+    h, hp = _i32(hist_len)
+    n = h.shape[0]
+    if len(keep) != n or len(tier_k) != n or len(tier_v) != n:
+        raise ValueError("one entry per conversation expected")
+    ptr = lambda t: int(t.data_ptr()) if hasattr(t, "data_ptr") else int(t)
+    pk = (C.c_void_p * n)(*[ptr(t) for t in tier_k])
+    pv = (C.c_void_p * n)(*[ptr(t) for t in tier_v])
+    out = np.zeros(n, dtype=np.int32)
+    i32p = C.POINTER(C.c_int32)
+    if all(isinstance(k, (int, np.integer)) for k in keep):
+        ks, ksp = _i32(keep)
+        st = lib.ca_tier_compact(n, hp, ksp, None, None, int(row_bytes), pk, pv, out.ctypes.data_as(i32p))
+    else:
+        flat = np.array([x for rs in keep for r in rs for x in r], dtype=np.int32).reshape(-1)
+        cnt = np.array([len(rs) for rs in keep], dtype=np.int32)
+        st = lib.ca_tier_compact(n, hp, None, flat.ctypes.data_as(i32p) if flat.size else (C.c_int32 * 1)(), cnt.ctypes.data_as(i32p),
+                                 int(row_bytes), pk, pv, out.ctypes.data_as(i32p))
+    if st != 0:
+        raise CaError(st, "ca_tier_compact rejected its arguments")
+    return out
 
 
 class Context:

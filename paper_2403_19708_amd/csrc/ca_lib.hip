@@ -423,6 +423,51 @@ ca_status ca_truncate_plan_sinks(const int32_t *hist_len, const int32_t *new_len
     return CA_OK;
 }
 
+ca_status ca_tier_compact(int32_t n, const int32_t *hist_len, const int32_t *keep_start, const int32_t *keep_ranges,
+                          const int32_t *keep_range_count, int64_t row_bytes, void *const *tier_k, void *const *tier_v,
+                          int32_t *hist_len_out) {
+    if (n < 0 || !hist_len || !tier_k || !tier_v || !hist_len_out || row_bytes <= 0) return CA_ERR_INVALID_ARG;
+    if ((keep_ranges == nullptr) != (keep_range_count == nullptr)) return CA_ERR_INVALID_ARG;
+    if (!keep_ranges && !keep_start) return CA_ERR_INVALID_ARG;
+    // everything is checked before the first byte moves
+    int64_t at = 0;
+    for (int32_t c = 0; c < n; ++c) {
+        if (hist_len[c] < 0) return CA_ERR_INVALID_ARG;
+        if (keep_ranges) {
+            if (keep_range_count[c] < 0) return CA_ERR_INVALID_ARG;
+            int32_t prev_end = 0;
+            for (int32_t r = 0; r < keep_range_count[c]; ++r, ++at) {
+                const int32_t b = keep_ranges[2 * at], e = keep_ranges[2 * at + 1];
+                if (b < prev_end || e <= b || e > hist_len[c]) return CA_ERR_OUT_OF_RANGE;
+                prev_end = e;
+            }
+            if (keep_range_count[c] > 0 && (!tier_k[c] || !tier_v[c])) return CA_ERR_INVALID_ARG;
+        } else {
+            if (keep_start[c] < 0 || keep_start[c] > hist_len[c]) return CA_ERR_OUT_OF_RANGE;
+            if (keep_start[c] < hist_len[c] && (!tier_k[c] || !tier_v[c])) return CA_ERR_INVALID_ARG;
+        }
+    }
+    at = 0;
+    for (int32_t c = 0; c < n; ++c) {
+        int64_t dst = 0;   // rows written so far; a range never starts below it, so the moves go towards lower addresses
+        auto move = [&](int32_t b, int32_t e) {
+            const size_t bytes = (size_t)(e - b) * (size_t)row_bytes;
+            if (b != dst) {
+                std::memmove((uint8_t *)tier_k[c] + (size_t)dst * row_bytes, (const uint8_t *)tier_k[c] + (size_t)b * row_bytes, bytes);
+                std::memmove((uint8_t *)tier_v[c] + (size_t)dst * row_bytes, (const uint8_t *)tier_v[c] + (size_t)b * row_bytes, bytes);
+            }
+            dst += e - b;
+        };
+        if (keep_ranges) {
+            for (int32_t r = 0; r < keep_range_count[c]; ++r, ++at) move(keep_ranges[2 * at], keep_ranges[2 * at + 1]);
+        } else if (keep_start[c] < hist_len[c]) {
+            move(keep_start[c], hist_len[c]);
+        }
+        hist_len_out[c] = (int32_t)dst;
+    }
+    return CA_OK;
+}
+
 ca_status ca_truncate_plan(const int32_t *hist_len, const int32_t *new_len, int32_t window, double ratio,
                            int32_t policy, int32_t n, int32_t *keep_start_out) {
     if (!hist_len || !new_len || !keep_start_out || n < 0) return CA_ERR_INVALID_ARG;

@@ -94,3 +94,50 @@ def test_discarding_list_load_and_attention(tier, kind):
             check_contract(w(got[at:at + int(new[c])]), ref, c)
             check_tight(w(got[at:at + int(new[c])]), ref, int(n_keep[c]), c)
             at += int(new[c])
+
+
+def test_compacted_tier_serves_the_next_turn_like_the_discarding_list():
+    """After ca_tier_compact has dropped the discarded rows from the pinned tier, loading everything that is left
+    gives the pool bytes and the attention output, bit for bit, that loading the kept ranges of the uncompacted tier
+    gave; the compacted tier holds the oracle's rows."""
+    Hq, Hkv, D, W = 8, 2, 128, 1024
+    hist = np.array([700, 333, 90], np.int32)
+    new = np.array([60, 9, 140], np.int32)
+    B, seed = len(hist), 85
+    keep = [scattered_ranges(int(hist[0]), 5)[:50], [(0, 4), (200, 333)], [(0, 90)]]
+    n_keep = np.array([len(ranges_to_indices(r)) for r in keep], np.int32)
+    full_k = [draw_values_bf16((int(hist[c] + new[c]), Hkv, D), seed, 10 + c) for c in range(B)]
+    full_v = [draw_values_bf16((int(hist[c] + new[c]), Hkv, D), seed, 20 + c) for c in range(B)]
+    dev = torch.device("cuda:0")
+    tier_k = [bits_to_torch(full_k[c][:hist[c]], pin=True) for c in range(B)]
+    tier_v = [bits_to_torch(full_v[c][:hist[c]], pin=True) for c in range(B)]
+    pages = (n_keep + new + P - 1) // P
+    num_pages = int(pages.sum()) + 5
+    bt = draw_block_table(pages, num_pages, seed)
+    take = lambda full: bits_to_torch(np.concatenate([full[c][hist[c]:] for c in range(B)]), dev)
+    kn, vn = take(full_k), take(full_v)
+    q = bits_to_torch(np.concatenate([draw_values_bf16((int(new[c]), Hq, D), seed, 30 + c) for c in range(B)]), dev)
+    cfg = ca.Config(n_layers=1, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, max_positions=W, max_seqs=B,
+                    max_batch_kv_tokens=int((n_keep + new).sum()) + 64, max_batch_q_tokens=int(new.sum()) + 16)
+
+    def turn(ctx, hist_now, keep_ranges):
+        k_pool = torch.zeros((num_pages, Hkv, P, D), dtype=torch.bfloat16, device=dev)
+        v_pool = torch.zeros_like(k_pool)
+        out = torch.zeros_like(q)
+        ctx.rope_rebase(hist_now, None if keep_ranges is not None else np.zeros(B, np.int32), new, bt, num_pages, keep_ranges=keep_ranges)
+        ctx.kv_load_layer(0, tier_k, tier_v, k_pool, v_pool)
+        ctx.kv_append_layer(0, kn, vn, k_pool, v_pool)
+        ctx.cached_prefill_attn(0, q, k_pool, v_pool, out, 1.0 / np.sqrt(D))
+        ctx.sync(); torch.cuda.synchronize()
+        return torch_to_bits(k_pool).copy(), torch_to_bits(v_pool).copy(), torch_to_bits(out).copy()
+
+    with ca.Context(cfg) as ctx:
+        before = turn(ctx, hist, keep)
+        left = ca.tier_compact(hist, keep, Hkv * D * 2, tier_k, tier_v)
+        assert np.array_equal(left, n_keep)
+        for c in range(B):
+            assert np.array_equal(torch_to_bits(tier_k[c])[:left[c]], oracle.compact_tier(full_k[c][:hist[c]], keep[c])), c
+            assert np.array_equal(torch_to_bits(tier_v[c])[:left[c]], oracle.compact_tier(full_v[c][:hist[c]], keep[c])), c
+        after = turn(ctx, left, None)
+    for a, b in zip(before, after):
+        assert np.array_equal(a, b)

@@ -171,3 +171,48 @@ def test_batch_validation_of_kept_ranges(lib):
         assert e.value.status_name == status, bad
     with pytest.raises(ca.CaError):
         ca.batch_validate(cfg, h, None, n, bt, p)                           # neither keep_start nor ranges
+
+
+def test_tier_compaction_agrees_with_oracle(lib):
+    """ca_tier_compact moves the kept rows of every conversation to the front of its host buffers, in place:
+    random range lists (adjacent, touching the ends, empty, everything), and the keep_start form."""
+    rng = np.random.default_rng(21)
+    row_bytes = 48
+    for trial in range(40):
+        B = int(rng.integers(1, 6))
+        hist = rng.integers(0, 60, B).astype(np.int32)
+        K = [rng.integers(0, 256, (int(h), row_bytes), dtype=np.uint8) for h in hist]
+        V = [rng.integers(0, 256, (int(h), row_bytes), dtype=np.uint8) for h in hist]
+        ranges = []
+        for h in hist:
+            cuts = np.sort(rng.choice(int(h) + 1, size=min(int(h) + 1, 2 * int(rng.integers(0, 4))), replace=False))
+            ranges.append([(int(cuts[i]), int(cuts[i + 1])) for i in range(0, len(cuts) - 1, 2)])
+        want_k = [oracle.compact_tier(k, r) for k, r in zip(K, ranges)]
+        want_v = [oracle.compact_tier(v, r) for v, r in zip(V, ranges)]
+        kb, vb = [k.copy() for k in K], [v.copy() for v in V]
+        left = ca.tier_compact(hist, ranges, row_bytes, [k.ctypes.data for k in kb], [v.ctypes.data for v in vb])
+        for c in range(B):
+            assert left[c] == len(want_k[c]), (trial, c)
+            assert np.array_equal(kb[c][:left[c]], want_k[c]) and np.array_equal(vb[c][:left[c]], want_v[c]), (trial, c)
+        # the truncation form: one suffix per conversation
+        ks = np.array([int(rng.integers(0, h + 1)) for h in hist], dtype=np.int32)
+        kb, vb = [k.copy() for k in K], [v.copy() for v in V]
+        left = ca.tier_compact(hist, [int(x) for x in ks], row_bytes, [k.ctypes.data for k in kb], [v.ctypes.data for v in vb])
+        for c in range(B):
+            assert left[c] == hist[c] - ks[c]
+            assert np.array_equal(kb[c][:left[c]], K[c][ks[c]:]) and np.array_equal(vb[c][:left[c]], V[c][ks[c]:])
+
+
+def test_tier_compaction_rejects_bad_ranges_and_moves_nothing(lib):
+    rows = np.arange(10 * 8, dtype=np.uint8).reshape(10, 8)
+    for bad in ([(0, 4), (3, 6)], [(5, 5)], [(6, 2)], [(0, 11)], [(4, 6), (0, 2)], [(-1, 2)]):
+        k, v = rows.copy(), rows.copy()
+        with pytest.raises(ca.CaError) as e:
+            ca.tier_compact([10], [bad], 8, [k.ctypes.data], [v.ctypes.data])
+        assert e.value.status_name == "CA_ERR_OUT_OF_RANGE", bad
+        assert np.array_equal(k, rows) and np.array_equal(v, rows)
+    # a later conversation's bad range must leave the earlier ones untouched as well
+    k0, v0, k1, v1 = rows.copy(), rows.copy(), rows.copy(), rows.copy()
+    with pytest.raises(ca.CaError):
+        ca.tier_compact([10, 10], [[(2, 4)], [(3, 2)]], 8, [k0.ctypes.data, k1.ctypes.data], [v0.ctypes.data, v1.ctypes.data])
+    assert np.array_equal(k0, rows) and np.array_equal(k1, rows)
