@@ -221,9 +221,11 @@ ca_status ca_rebase_read(ca_ctx *ctx, int32_t which, int32_t *out, int64_t capac
  * tokens of its kept ranges in order -- become context tokens [0, n_keep[c]).
  * Truncation and discarding are just source offsets.  Runs on the internal copy-in and unpack streams and
  * marks the layer ready; ca_cached_prefill_attn(layer) waits for that mark on its own stream.
- * Sources: pinned host memory (staged hipMemcpyAsync into a ring slot + unpack kernel, or read
- * in place by the unpack kernel, see load_mode) or device memory (read in place).  A layer can
- * be loaded once per plan (CA_ERR_NOT_READY otherwise).                                        */
+ * Sources: pinned host memory (staged hipMemcpyAsync into a ring slot + unpack kernel -- the K
+ * half is copied on the copy-in stream and the V half on the unpack stream, two copy queues
+ * keeping the host link busier than one -- or read in place by the unpack kernel, see load_mode)
+ * or device memory (read in place).  A layer can be loaded once per plan (CA_ERR_NOT_READY
+ * otherwise).                                                                                  */
 ca_status ca_kv_load_layer(ca_ctx *ctx, int32_t layer, const void *const *src_k,
                            const void *const *src_v, void *k_pool, void *v_pool);
 
