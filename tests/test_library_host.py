@@ -216,3 +216,18 @@ def test_tier_compaction_rejects_bad_ranges_and_moves_nothing(lib):
     with pytest.raises(ca.CaError):
         ca.tier_compact([10, 10], [[(2, 4)], [(3, 2)]], 8, [k0.ctypes.data, k1.ctypes.data], [v0.ctypes.data, v1.ctypes.data])
     assert np.array_equal(k0, rows) and np.array_equal(k1, rows)
+
+
+def test_entry_points_reject_a_null_context_without_touching_a_gpu(lib):
+    """Every call that takes a context checks it first: a NULL context is an argument error, not a crash."""
+    import ctypes as C
+    n = C.c_int64(0)
+    ms = C.c_double(0.0)
+    assert lib.ca_profile_enable(None, 1) == 1                                           # CA_ERR_INVALID_ARG
+    assert lib.ca_profile_read(None, 0, C.byref(ms), C.byref(n)) == 1
+    assert lib.ca_profile_timeline(None, None, None, None, 0, C.byref(n)) == 1
+    assert lib.ca_sync(None) == 1
+    assert lib.ca_join(None, None) == 1
+    assert lib.ca_kv_load_layer(None, 0, None, None, None, None) == 1
+    assert lib.ca_kv_append_save_layer(None, 0, None, None, None, None, None, None, None) == 1
+    assert lib.ca_cached_prefill_attn_static(None, 0, None, None, None, None, C.c_float(1.0), None) == 1
